@@ -1,0 +1,182 @@
+"""Benchmark of the CSER update on one MI355X.
+
+A "step" is one call of cser_step: block selection, the fused local step + partial synchronisation
++ residual bookkeeping, and the error reset on the iterations where t mod H = 0 -- the whole hot
+path.  The workload is the large-CNN-sized configuration the headline metric is quoted on
+(d = 25,557,032, W = 8, block 1024, R_step 256, R_reset 16, H 32); states and two rotating gradient
+buffers are resident in HBM before the timed region, gradients are synthetic N(0, 1e-3).
+
+Prints one JSON line: whole-job param-elements/s, the HBM roofline of the fused-step kernel
+(algorithmic bytes per launch / HIP-event duration per launch, measured in the same timed region),
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
+
+
+def step_bytes(wl, d_sel, with_error=True, with_momentum=True):
+    """Algorithmic bytes of one fused-step launch: per element and worker read g, m, x, e and write
+    m, x, e (28 B); on the d_sel columns of chosen blocks e is neither read nor written (20 B)."""
+    per = 4 * (1 + (2 if with_momentum else 0) + 2 + (2 if with_error else 0))
+    sel = per - (8 if with_error else 0)
+    return wl.W * (per * (wl.d - d_sel) + sel * d_sel)
+
+
+def chosen_columns(wl, mask):
+    """Number of columns in the blocks a mask selects (the last block may be short)."""
+    n = int(mask.sum()) * wl.block
+    if mask[-1]:
+        n -= wl.B * wl.block - wl.d
+    return n
+
+
+def read_traffic(workload):
+    """HBM bytes per fused-step launch from the committed counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"fused_step_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(wl, seconds_target=15.0):
+    """The oracle as it stands, one host thread, on a slice of the workload's blocks."""
+    import numpy as np
+    from oracle import reference as R
+    steps = wl.H                                   # one full reset period, so the reset is included
+    nb = max(1, wl.B // 8)
+    ncols = min(wl.d, nb * wl.block)
+    rng = np.random.default_rng(wl.seed)
+    x0 = (rng.standard_normal(ncols) * np.sqrt(wl.x_var)).astype(np.float32)
+    g = [(rng.standard_normal((wl.W, ncols)) * np.sqrt(wl.g_var)).astype(np.float32) for _ in range(2)]
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, x0,
+                     dtype=np.float32, b0=0, b1=nb)
+    t0 = time.perf_counter()
+    for t in range(steps):
+        o.step(g[t & 1])
+    dt = time.perf_counter() - t0
+    return {"value": ncols * steps / dt, "unit": "param-elements/s", "cores": 1, "kind": "oracle",
+            "sample": f"blocks [0, {nb}) of {wl.B} ({ncols} of {wl.d} columns, all {wl.W} workers), {steps} steps "
+                      f"incl. one error reset, block choice over all blocks; {dt:.1f} s on one host thread",
+            "host_cpus": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="large_cnn")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wg-cap", type=int, default=None)
+    ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (all W worker states are resident on it and the worker "
+                 "average is a reduction over rows, not a collective); --gpus must be 1")
+
+    import torch
+    from paper_2007_13221_amd import binding as B
+    from paper_2007_13221_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    wl = I.WORKLOADS[args.workload]
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, I.initial_model(wl, dev))
+    if args.wg_cap is not None:
+        B.cser_set_tuning(opt.ctx, 0, args.wg_cap)
+    if args.nontemporal is not None:
+        B.cser_set_tuning(opt.ctx, 1, args.nontemporal)
+    if args.batch is not None:
+        B.cser_set_tuning(opt.ctx, 2, args.batch)
+    grads = [I.gradient(wl, t, dev) for t in (1, 2)]   # generated outside every timed region
+    torch.cuda.synchronize()
+
+    for t in range(args.warmup):
+        opt.step(grads[t & 1])
+    torch.cuda.synchronize()
+
+    B.cser_profile_enable(opt.ctx, True)
+    B.cser_profile_clear(opt.ctx)
+    t_first = B.cser_get_step(opt.ctx) + 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        opt.step(grads[t & 1])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    step_ms, step_launches = B.cser_profile_read(opt.ctx, 0)
+    reset_ms, reset_launches = B.cser_profile_read(opt.ctx, 1)
+    B.cser_profile_enable(opt.ctx, False)
+
+    # algorithmic bytes of the timed launches (block lists recomputed by the GPU selector afterwards)
+    total_step_bytes = 0
+    total_reset_bytes = 0
+    for t in range(t_first, t_first + args.steps):
+        _, mask = B.cser_select_blocks(opt.ctx, 0, t)
+        total_step_bytes += step_bytes(wl, chosen_columns(wl, mask))
+        if wl.H and t % wl.H == 0:
+            _, rmask = B.cser_select_blocks(opt.ctx, 1, t)
+            total_reset_bytes += 16 * wl.W * chosen_columns(wl, rmask)
+    bytes_per_launch = total_step_bytes / args.steps
+    kernel_ms = step_ms / max(step_launches, 1)
+    achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
+
+    # practical ceiling: a plain 128-bit copy kernel over buffers of the same total size class
+    n_copy = wl.W * wl.ld * 4
+    src, dst = opt.m, torch.empty_like(opt.m)
+    for _ in range(3):
+        B.cser_copy_probe(dst, src, n_copy)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(20):
+        B.cser_copy_probe(dst, src, n_copy)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * n_copy * 20 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del dst
+
+    out = {
+        "metric": "CSER step param-elements/s and achieved HBM GB/s (% of peak) at d=25.6M, W=8",
+        "value": wl.d * args.steps / elapsed,
+        "unit": "param-elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: d={wl.d}, W={wl.W}, block={wl.block}, R_step={wl.R_step}, "
+                               f"R_reset={wl.R_reset}, H={wl.H}, lr={wl.lr}, momentum={wl.momentum}, "
+                               f"g~N(0,{wl.g_var}), seed={wl.seed}; steps t={t_first}..{t_first + args.steps - 1}",
+                   "resident": "x, e, m [W][ld] fp32 + 2 rotating g buffers", "ld": wl.ld},
+        "worker_elements_per_s": wl.W * wl.d * args.steps / elapsed,
+        "whole_path_GBps": (total_step_bytes + total_reset_bytes) / elapsed / 1e9,
+        "whole_path_frac_of_peak": (total_step_bytes + total_reset_bytes) / elapsed / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "cser_step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(wl.name),
+                     "bytes_per_launch": bytes_per_launch, "ms_per_launch": kernel_ms, "launches": step_launches},
+        "reset_kernel": {"launches": reset_launches, "ms_per_launch": reset_ms / max(reset_launches, 1),
+                         "bytes_per_launch": total_reset_bytes / max(reset_launches, 1)},
+        "copy_kernel_GBps": copy_gbps,
+    }
+    opt.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,153 @@
+/*
+ * cser.h -- C ABI of the MI355X-native CSER optimizer update (arxiv 2007.13221).
+ *
+ * One call of cser_step() is one iteration t of the paper's Algorithm 3 (M-CSER, Section 3.2;
+ * Algorithm 2 when momentum = 0) for all n = W workers at once, from the point where the
+ * stochastic gradients g_{i,t} are known:
+ *
+ *     m_i <- beta m_i + g_i ;  p_i <- eta (beta m_i + g_i)              (Get_p, Appendix A.4)
+ *     p'_i, r_i <- PSync(p_i, C_step)                                    (Algorithm PSync, Section 3.1)
+ *     x_i <- x_i - p'_i ;  e_i <- e_i - r_i
+ *     if t mod H = 0:  e'_i, e_i <- PSync(e_i, C_reset) ;  x_i <- x_i - e_i(old) + e'_i     (error reset)
+ *
+ * C_step and C_reset are globally-randomized blockwise sparsifiers (GRBS, Definition 2,
+ * Section 3.3): the flat d-vector is cut into B = ceil(d / block) blocks and every worker keeps
+ * the same k = ceil(B / R) randomly drawn blocks, a pure function of (seed, t).  C_step is the
+ * compressor the paper calls C_2 (ratio R_C2, used every iteration), C_reset the one it calls
+ * C_1 (ratio R_C1, used every H iterations); the names used here say what they do because the
+ * paper's numbering is easy to swap.
+ *
+ * All W worker states live on ONE GPU as row-major fp32 matrices [W][ld]; the worker average
+ * inside PSync is a reduction over the rows, not a collective.
+ *
+ * Conventions for every entry point
+ *   - returns CSER_OK (0) or a negative cser_status; nothing is thrown, nothing aborts;
+ *   - "device" pointers are HIP device addresses, "host" pointers ordinary memory;
+ *   - kernels are enqueued on the hipStream_t passed as `void* hip_stream` (NULL = the null
+ *     stream) and the call returns without waiting for them;
+ *   - a context is bound to the device that was current at cser_create() and must be used with
+ *     that device current; calls on one context must not overlap each other.
+ */
+#ifndef CSER_H
+#define CSER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cser_status {
+  CSER_OK = 0,
+  CSER_EINVAL = -1,  /* null pointer, zero size, ld < d, R_reset = 0, beta outside [0,1), non-finite eta ... */
+  CSER_EALIGN = -2,  /* a device pointer is not 4-byte aligned                                            */
+  CSER_ENOMEM = -3,  /* host or device allocation failed                                                  */
+  CSER_EHIP = -4,    /* a HIP runtime call failed; cser_last_hip_error() names it                          */
+  CSER_ERANGE = -5   /* a size is beyond what the kernels index (B >= 2^32 or d/4 >= 2^32)                 */
+} cser_status;
+
+typedef struct cser_ctx cser_ctx; /* opaque, host-side */
+
+typedef struct cser_config {
+  uint64_t d;        /* parameters per worker, >= 1                                                       */
+  uint64_t ld;       /* row stride of x, e, m, g in elements, >= d                                        */
+  uint32_t W;        /* number of workers n, >= 1 (Section 3)                                             */
+  uint32_t block;    /* elements per GRBS block, >= 1; B = ceil(d / block) (Definition 2)                 */
+  uint32_t R_step;   /* ratio of the per-iteration compressor (paper: R_C2): keeps ceil(B / R_step)
+                        blocks; 1 = identity; 0 = the delta = 0 compressor C(v) = 0 (Section 3)          */
+  uint32_t R_reset;  /* ratio of the error-reset compressor (paper: R_C1), >= 1; 1 = full reset           */
+  uint32_t H;        /* error-reset interval (Algorithm 3 input); 0 = cser_step never resets              */
+  float lr;          /* eta                                                                               */
+  float momentum;    /* beta in [0, 1); 0 gives Algorithm 2                                               */
+  uint64_t seed;     /* the synchronized random seed of Section 3.3                                       */
+} cser_config;
+
+/*
+ * Create a context (Algorithm 3, "Initialize").
+ *   x  device [W][ld] fp32, in/out: the caller has written the same x_hat_0 into every row.
+ *   e  device [W][ld] fp32 or NULL.  Non-NULL: implementation I; cser_create zero-fills it.
+ *      NULL: implementation II of Appendix A.4 (no residual buffer; the reset averages x itself).
+ *   m  device [W][ld] fp32 or NULL.  Non-NULL: zero-filled here.  NULL is allowed only with
+ *      momentum = 0 (Algorithm 2 keeps no momentum) and removes the m traffic.
+ * The buffers stay owned by the caller, must outlive the context and are never freed here.  The
+ * context owns a few small device arrays (block masks and index lists).  The zero fills are
+ * enqueued on hip_stream.  Vectorised kernels are used when ld and block are multiples of 4 and
+ * the pointers are 16-byte aligned; any other layout runs element-wise kernels with the same
+ * results.  On failure *out is NULL.
+ */
+int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_stream, cser_ctx** out);
+
+/*
+ * One iteration: t <- t + 1; block selection for (seed, stream 0, t); the fused local step,
+ * partial synchronisation and residual bookkeeping (the four statements of Algorithm 3 before
+ * its "if"); then, when H > 0 and t mod H = 0, the error reset of cser_error_reset().
+ *   g  device [W][ld] fp32, read-only: this iteration's stochastic gradients, one row per worker.
+ * Arithmetic: beta*m+g and beta*m_new+g are single fused multiply-adds, the worker mean is the
+ * left-to-right sum over i = 0..W-1 divided by W, everything in fp32.
+ */
+int cser_step(cser_ctx* ctx, const float* g, void* hip_stream);
+
+/*
+ * The error-reset branch of Algorithm 3 at the current t: block selection for (seed, stream 1,
+ * t), then on the selected blocks  ebar = mean_i e_i ;  x_i <- (x_i - e_i) + ebar ;  e_i <- +0.
+ * (Implementation II: x_i <- mean_i x_i on the selected blocks.)  Exposed so that a caller can
+ * force a reset at any t.
+ */
+int cser_error_reset(cser_ctx* ctx, void* hip_stream);
+
+/* Free the context and its device arrays (not x, e, m).  cser_destroy(NULL) returns CSER_OK. */
+int cser_destroy(cser_ctx* ctx);
+
+/*
+ * Run the block selector (Definition 2; shared seed, Section 3.3) for iteration t and copy the
+ * result to host memory; synchronous.  which: 0 = C_step's stream, 1 = C_reset's stream.
+ *   idx_host   host, >= k entries or NULL: the chosen block ids in draw order pi(0..k-1)
+ *   mask_host  host, B bytes or NULL: 1 where the block is chosen
+ *   k_out      host or NULL: receives k
+ */
+int cser_select_blocks(cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host, uint8_t* mask_host,
+                       uint32_t* k_out);
+
+/* Sizes derived from the configuration: B, k_step = ceil(B/R_step), k_reset = ceil(B/R_reset). */
+int cser_block_counts(const cser_ctx* ctx, uint64_t* B, uint32_t* k_step, uint32_t* k_reset);
+
+/* Learning-rate schedules (Section 5.1): takes effect from the next cser_step. */
+int cser_set_lr(cser_ctx* ctx, float lr);
+
+/* The iteration counter t (0 after create; the state of a run is x, e, m, t and the seed). */
+int cser_get_step(const cser_ctx* ctx, uint64_t* t);
+int cser_set_step(cser_ctx* ctx, uint64_t t);
+
+/*
+ * Per-kernel timing.  When enabled, every launch of the fused-step kernel (which = 0) and of the
+ * reset kernel (which = 1) is bracketed by HIP events on the launch stream; cser_profile_read
+ * waits for the recorded events, adds their elapsed times and launch counts to running totals,
+ * returns the totals and recycles the events.  At most 4096 launches per kind are held between
+ * reads; later ones go untimed.
+ */
+int cser_profile_enable(cser_ctx* ctx, int on);
+int cser_profile_read(cser_ctx* ctx, int which, double* total_ms, uint64_t* launches);
+int cser_profile_clear(cser_ctx* ctx);
+
+/*
+ * Launch shape of the fused-step kernel, for measurement sweeps.  key 0: workgroup cap (0 = one
+ * 4-column group per lane; n > 0 = at most n workgroups, lanes loop); key 1: 1 = non-temporal
+ * loads/stores, 0 = ordinary; key 2: workers loaded per batch (1, 2, 4 or 8).  Results do not
+ * depend on these.
+ */
+int cser_set_tuning(cser_ctx* ctx, int key, int64_t value);
+
+/*
+ * Practical bandwidth ceiling: a plain copy kernel dst[i] = src[i] over n_bytes (device pointers,
+ * 16-byte aligned, n_bytes a multiple of 16), enqueued on hip_stream.  Used by the benchmark to
+ * report what the same access width achieves with no arithmetic.
+ */
+int cser_copy_probe(void* dst, const void* src, uint64_t n_bytes, void* hip_stream);
+
+const char* cser_strerror(int status);
+const char* cser_last_hip_error(void); /* text of the last HIP error seen by this thread, "" if none */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSER_H */

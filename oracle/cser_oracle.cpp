@@ -15,8 +15,11 @@
 //
 // The routines follow the algorithm boxes statement by statement on whole vectors
 // (restricted to a column range when the caller simulates a slice of the blocks);
-// there is no fusion of statements and no special-casing of selected / unselected
-// blocks: PSync really forms C(v), r = v - C(v), the worker mean of C(v), and mean + r.
+// there is no fusion of statements, and PSync really forms C(v), r = v - C(v), the worker
+// mean of C(v), and mean + r for every column.  The one place where chosen and unchosen
+// blocks are told apart is the model correction of the error reset, x <- x - e + e': where
+// the block is not chosen e' is identically e, and x is left untouched instead of being
+// sent through (x - e) + e, which is the identity only in exact arithmetic.
 //
 // Arithmetic contract (the paper fixes no precision; these are this build's readings):
 //   * `real` is float (the resident-state precision) or double (a truth run used to
@@ -248,7 +251,11 @@ void mcser_error_reset(const Problem& pb, uint64_t t, uint64_t R_reset, real* x,
   psync(pb, chosen, ehalf, eprime, r);
   for (uint32_t i = 0; i < pb.W; ++i)
     for (uint64_t j = 0; j < n; ++j) {
-      x[i * pb.ld + j] = (x[i * pb.ld + j] - ehalf[i * n + j]) + eprime[i * n + j];
+      // Outside the chosen blocks C(e) = 0 on every worker, so e' = 0 + r = e exactly and the
+      // correction -e + e' is identically zero: x is left as it is there.  (Evaluating (x - e) + e
+      // in floating point would perturb x by a rounding on blocks the reset does not concern.)
+      if (chosen[(pb.col0 + j) / pb.block])
+        x[i * pb.ld + j] = (x[i * pb.ld + j] - ehalf[i * n + j]) + eprime[i * n + j];
       e[i * pb.ld + j] = r[i * n + j];
     }
 }

@@ -1,0 +1,210 @@
+"""Thin ctypes binding of the C ABI in include/cser.h: same names, argument marshalling only.
+
+Every step of the update runs in the HIP kernels of libcser_hip.so; this module never computes
+anything and has no fallback: if the library is missing or does not load, the first call raises.
+PyTorch appears only as the owner of device memory (tensors) and of the current stream.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIBRARY = os.path.join(_HERE, "libcser_hip.so")
+
+CSER_OK, CSER_EINVAL, CSER_EALIGN, CSER_ENOMEM, CSER_EHIP, CSER_ERANGE = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ("cser_create", "cser_step", "cser_error_reset", "cser_destroy", "cser_select_blocks",
+           "cser_block_counts", "cser_set_lr", "cser_get_step", "cser_set_step", "cser_profile_enable",
+           "cser_profile_read", "cser_profile_clear", "cser_set_tuning", "cser_copy_probe", "cser_strerror",
+           "cser_last_hip_error")
+
+
+class cser_config(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_uint64), ("ld", ctypes.c_uint64), ("W", ctypes.c_uint32),
+                ("block", ctypes.c_uint32), ("R_step", ctypes.c_uint32), ("R_reset", ctypes.c_uint32),
+                ("H", ctypes.c_uint32), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
+                ("seed", ctypes.c_uint64)]
+
+
+class CSERError(RuntimeError):
+    def __init__(self, status, where):
+        text = _lib().cser_strerror(status).decode()
+        detail = _lib().cser_last_hip_error().decode() if status == CSER_EHIP else ""
+        super().__init__(f"{where}: {text} ({status})" + (f": {detail}" if detail else ""))
+        self.status = status
+
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIBRARY):
+            raise RuntimeError(f"{LIBRARY} is missing: build it with `python -m paper_2007_13221_amd.build` "
+                               "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIBRARY)
+        vp, u64, u32, i64 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int64
+        L.cser_create.argtypes = [ctypes.POINTER(cser_config), vp, vp, vp, vp, ctypes.POINTER(vp)]
+        L.cser_step.argtypes = [vp, vp, vp]
+        L.cser_error_reset.argtypes = [vp, vp]
+        L.cser_destroy.argtypes = [vp]
+        L.cser_select_blocks.argtypes = [vp, ctypes.c_int, u64, vp, vp, ctypes.POINTER(u32)]
+        L.cser_block_counts.argtypes = [vp, ctypes.POINTER(u64), ctypes.POINTER(u32), ctypes.POINTER(u32)]
+        L.cser_set_lr.argtypes = [vp, ctypes.c_float]
+        L.cser_get_step.argtypes = [vp, ctypes.POINTER(u64)]
+        L.cser_set_step.argtypes = [vp, u64]
+        L.cser_profile_enable.argtypes = [vp, ctypes.c_int]
+        L.cser_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(u64)]
+        L.cser_profile_clear.argtypes = [vp]
+        L.cser_set_tuning.argtypes = [vp, ctypes.c_int, i64]
+        L.cser_copy_probe.argtypes = [vp, vp, u64, vp]
+        L.cser_strerror.argtypes = [ctypes.c_int]
+        L.cser_strerror.restype = ctypes.c_char_p
+        L.cser_last_hip_error.argtypes = []
+        L.cser_last_hip_error.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name not in ("cser_strerror", "cser_last_hip_error"):
+                getattr(L, name).restype = ctypes.c_int
+        _LIB = L
+    return _LIB
+
+
+def _check(status, where):
+    if status != CSER_OK:
+        raise CSERError(status, where)
+
+
+def _ptr(t):
+    """Device address of a torch tensor (or None, or a raw integer address)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    """Raw hipStream_t: None means torch's current stream."""
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def cser_create(cfg: cser_config, x, e, m, stream=None):
+    """x, e, m: device tensors [W][ld] fp32 (e and/or m may be None, see cser.h). Returns a handle."""
+    handle = ctypes.c_void_p()
+    _check(_lib().cser_create(ctypes.byref(cfg), _ptr(x), _ptr(e), _ptr(m), _stream(stream), ctypes.byref(handle)),
+           "cser_create")
+    return handle
+
+
+def cser_step(ctx, g, stream=None):
+    _check(_lib().cser_step(ctx, _ptr(g), _stream(stream)), "cser_step")
+
+
+def cser_error_reset(ctx, stream=None):
+    _check(_lib().cser_error_reset(ctx, _stream(stream)), "cser_error_reset")
+
+
+def cser_destroy(ctx):
+    _check(_lib().cser_destroy(ctx), "cser_destroy")
+
+
+def cser_block_counts(ctx):
+    B, ks, kr = ctypes.c_uint64(), ctypes.c_uint32(), ctypes.c_uint32()
+    _check(_lib().cser_block_counts(ctx, ctypes.byref(B), ctypes.byref(ks), ctypes.byref(kr)), "cser_block_counts")
+    return B.value, ks.value, kr.value
+
+
+def cser_select_blocks(ctx, which, t):
+    """Returns (idx[k] uint32 in draw order, mask[B] uint8) as numpy arrays."""
+    B, ks, kr = cser_block_counts(ctx)
+    k = ks if which == 0 else kr
+    idx = np.zeros(max(k, 1), dtype=np.uint32)
+    mask = np.zeros(B, dtype=np.uint8)
+    kout = ctypes.c_uint32()
+    _check(_lib().cser_select_blocks(ctx, int(which), int(t), idx.ctypes.data, mask.ctypes.data, ctypes.byref(kout)),
+           "cser_select_blocks")
+    assert kout.value == k
+    return idx[:k], mask
+
+
+def cser_set_lr(ctx, lr):
+    _check(_lib().cser_set_lr(ctx, float(lr)), "cser_set_lr")
+
+
+def cser_get_step(ctx):
+    t = ctypes.c_uint64()
+    _check(_lib().cser_get_step(ctx, ctypes.byref(t)), "cser_get_step")
+    return t.value
+
+
+def cser_set_step(ctx, t):
+    _check(_lib().cser_set_step(ctx, int(t)), "cser_set_step")
+
+
+def cser_profile_enable(ctx, on=True):
+    _check(_lib().cser_profile_enable(ctx, 1 if on else 0), "cser_profile_enable")
+
+
+def cser_profile_read(ctx, which):
+    """Returns (total_ms, launches) of the fused-step kernel (which=0) or the reset kernel (which=1)."""
+    ms, n = ctypes.c_double(), ctypes.c_uint64()
+    _check(_lib().cser_profile_read(ctx, int(which), ctypes.byref(ms), ctypes.byref(n)), "cser_profile_read")
+    return ms.value, n.value
+
+
+def cser_profile_clear(ctx):
+    _check(_lib().cser_profile_clear(ctx), "cser_profile_clear")
+
+
+def cser_set_tuning(ctx, key, value):
+    _check(_lib().cser_set_tuning(ctx, int(key), int(value)), "cser_set_tuning")
+
+
+def cser_copy_probe(dst, src, n_bytes, stream=None):
+    _check(_lib().cser_copy_probe(_ptr(dst), _ptr(src), int(n_bytes), _stream(stream)), "cser_copy_probe")
+
+
+def cser_strerror(status):
+    return _lib().cser_strerror(int(status)).decode()
+
+
+def make_config(d, W, block, R_step, R_reset, H, lr, momentum, seed, ld=None) -> cser_config:
+    return cser_config(int(d), int(d if ld is None else ld), int(W), int(block), int(R_step), int(R_reset),
+                       int(H), float(lr), float(momentum), int(seed))
+
+
+class CSER:
+    """Convenience owner of a context and its state tensors (allocation and lifetime only)."""
+
+    def __init__(self, cfg: cser_config, x, with_error=True, with_momentum=True, stream=None):
+        import torch
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and tuple(x.shape) == (cfg.W, cfg.ld)
+        self.cfg = cfg
+        self.x = x
+        self.e = torch.zeros_like(x) if with_error else None
+        self.m = torch.zeros_like(x) if with_momentum else None
+        self.ctx = cser_create(cfg, self.x, self.e, self.m, stream)
+
+    def step(self, g, stream=None):
+        cser_step(self.ctx, g, stream)
+
+    def error_reset(self, stream=None):
+        cser_error_reset(self.ctx, stream)
+
+    def close(self):
+        if self.ctx is not None:
+            cser_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

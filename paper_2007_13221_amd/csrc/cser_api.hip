@@ -1,0 +1,359 @@
+// C ABI of the CSER update (declared in include/cser.h): argument checks, the context, the
+// iteration counter of Algorithm 3 and the order in which the kernels are enqueued.  No arithmetic
+// of the method happens on the host.
+
+#include "../../include/cser.h"
+#include "cser_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_last_hip_error;
+
+int hip_failed(hipError_t err, const char* what) {
+  g_last_hip_error = std::string(what) + ": " + hipGetErrorString(err);
+  return CSER_EHIP;
+}
+
+#define CSER_HIP(call)                                     \
+  do {                                                     \
+    hipError_t err__ = (call);                             \
+    if (err__ != hipSuccess) return hip_failed(err__, #call); \
+  } while (0)
+
+constexpr size_t kMaxTimedLaunches = 4096;
+
+struct Timer {
+  std::vector<hipEvent_t> begin, end;   // pooled events, created on first use
+  size_t used = 0;
+  double total_ms = 0.0;
+  uint64_t launches = 0;
+};
+
+uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+struct cser_ctx {
+  cser_config cfg;
+  float* x;
+  float* e;
+  float* m;
+  uint64_t B;
+  uint32_t k_step, k_reset;
+  uint64_t t;
+  bool vector_layout;        // ld, block multiples of 4 and x, e, m 16-byte aligned
+  uint8_t* mask_step;        // device, B bytes
+  uint8_t* mask_reset;       // device, B bytes
+  uint32_t* idx_step;        // device, max(k_step, 1) entries
+  uint32_t* idx_reset;       // device, max(k_reset, 1) entries
+  uint8_t* mask_query;       // device scratch of cser_select_blocks, B bytes
+  uint32_t* idx_query;       // device scratch of cser_select_blocks, B entries (lazily allocated)
+  cser::Tuning tuning;
+  bool profiling;
+  Timer timers[2];
+};
+
+namespace {
+
+int record_begin(cser_ctx* ctx, int which, hipStream_t s, bool* timed) {
+  *timed = false;
+  if (!ctx->profiling) return CSER_OK;
+  Timer& tm = ctx->timers[which];
+  if (tm.used >= kMaxTimedLaunches) return CSER_OK;
+  if (tm.used == tm.begin.size()) {
+    hipEvent_t a, b;
+    CSER_HIP(hipEventCreate(&a));
+    hipError_t err = hipEventCreate(&b);
+    if (err != hipSuccess) {
+      hipEventDestroy(a);
+      return hip_failed(err, "hipEventCreate");
+    }
+    tm.begin.push_back(a);
+    tm.end.push_back(b);
+  }
+  CSER_HIP(hipEventRecord(tm.begin[tm.used], s));
+  *timed = true;
+  return CSER_OK;
+}
+
+int record_end(cser_ctx* ctx, int which, hipStream_t s, bool timed) {
+  if (!timed) return CSER_OK;
+  Timer& tm = ctx->timers[which];
+  CSER_HIP(hipEventRecord(tm.end[tm.used], s));
+  tm.used += 1;
+  return CSER_OK;
+}
+
+int drain_timer(Timer& tm) {
+  for (size_t i = 0; i < tm.used; ++i) {
+    CSER_HIP(hipEventSynchronize(tm.end[i]));
+    float ms = 0.0f;
+    CSER_HIP(hipEventElapsedTime(&ms, tm.begin[i], tm.end[i]));
+    tm.total_ms += ms;
+    tm.launches += 1;
+  }
+  tm.used = 0;
+  return CSER_OK;
+}
+
+void free_device_arrays(cser_ctx* ctx) {
+  if (ctx->mask_step) (void)hipFree(ctx->mask_step);
+  if (ctx->mask_reset) (void)hipFree(ctx->mask_reset);
+  if (ctx->idx_step) (void)hipFree(ctx->idx_step);
+  if (ctx->idx_reset) (void)hipFree(ctx->idx_reset);
+  if (ctx->mask_query) (void)hipFree(ctx->mask_query);
+  if (ctx->idx_query) (void)hipFree(ctx->idx_query);
+  for (Timer& tm : ctx->timers) {
+    for (hipEvent_t ev : tm.begin) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : tm.end) (void)hipEventDestroy(ev);
+  }
+}
+
+int validate(const cser_config* c, const float* x, const float* e, const float* m) {
+  if (!c || !x) return CSER_EINVAL;
+  if (c->d == 0 || c->W == 0 || c->block == 0 || c->ld < c->d) return CSER_EINVAL;
+  if (c->R_reset == 0) return CSER_EINVAL;
+  if (!std::isfinite(c->lr)) return CSER_EINVAL;
+  if (!(c->momentum >= 0.0f && c->momentum < 1.0f)) return CSER_EINVAL;
+  if (!m && c->momentum != 0.0f) return CSER_EINVAL;
+  if (!aligned(x, 4) || !aligned(e, 4) || !aligned(m, 4)) return CSER_EALIGN;
+  const uint64_t B = ceil_div(c->d, c->block);
+  if (B > 0xFFFFFFFFull) return CSER_ERANGE;
+  if (c->d / 4 > 0xFFFFFFFFull) return CSER_ERANGE;
+  return CSER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_stream, cser_ctx** out) {
+  if (!out) return CSER_EINVAL;
+  *out = nullptr;
+  const int bad = validate(cfg, x, e, m);
+  if (bad != CSER_OK) return bad;
+
+  cser_ctx* ctx = new (std::nothrow) cser_ctx();
+  if (!ctx) return CSER_ENOMEM;
+  ctx->cfg = *cfg;
+  ctx->x = x;
+  ctx->e = e;
+  ctx->m = m;
+  ctx->B = ceil_div(cfg->d, cfg->block);
+  ctx->k_step = cfg->R_step == 0 ? 0u : static_cast<uint32_t>(ceil_div(ctx->B, cfg->R_step));
+  ctx->k_reset = static_cast<uint32_t>(ceil_div(ctx->B, cfg->R_reset));
+  ctx->t = 0;
+  ctx->vector_layout = cfg->ld % 4 == 0 && cfg->block % 4 == 0 && aligned(x, 16) && aligned(e, 16) && aligned(m, 16);
+  if (!ctx->vector_layout && cfg->d > 0xFFFFFFFFull) {
+    delete ctx;
+    return CSER_ERANGE;   // the element-wise kernels index columns with 32 bits
+  }
+  ctx->profiling = false;
+
+  hipError_t err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_step), ctx->B);
+  if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_reset), ctx->B);
+  if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_query), ctx->B);
+  if (err == hipSuccess)
+    err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_step), sizeof(uint32_t) * (ctx->k_step ? ctx->k_step : 1u));
+  if (err == hipSuccess)
+    err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_reset), sizeof(uint32_t) * (ctx->k_reset ? ctx->k_reset : 1u));
+  if (err != hipSuccess) {
+    free_device_arrays(ctx);
+    delete ctx;
+    if (err == hipErrorOutOfMemory) return CSER_ENOMEM;
+    return hip_failed(err, "hipMalloc");
+  }
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint64_t n = static_cast<uint64_t>(cfg->W - 1) * cfg->ld + cfg->d;   // up to the last row's last column
+  if (e) err = cser::launch_fill_zero(e, n, s);
+  if (err == hipSuccess && m) err = cser::launch_fill_zero(m, n, s);
+  if (err != hipSuccess) {
+    free_device_arrays(ctx);
+    delete ctx;
+    return hip_failed(err, "zero fill");
+  }
+  *out = ctx;
+  return CSER_OK;
+}
+
+int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
+  if (!ctx) return CSER_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (ctx->k_reset == 0) return CSER_OK;
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, static_cast<uint32_t>(ctx->B), ctx->k_reset,
+                                 ctx->mask_reset, ctx->idx_reset, s));
+  cser::ResetParams p;
+  p.x = ctx->x;
+  p.e = ctx->e;
+  p.idx = ctx->idx_reset;
+  p.ld = ctx->cfg.ld;
+  p.d = ctx->cfg.d;
+  p.W = ctx->cfg.W;
+  p.block = ctx->cfg.block;
+  p.k = ctx->k_reset;
+  bool timed = false;
+  int rc = record_begin(ctx, 1, s, &timed);
+  if (rc != CSER_OK) return rc;
+  CSER_HIP(cser::launch_reset(p, ctx->mask_reset, ctx->vector_layout, s));
+  return record_end(ctx, 1, s, timed);
+}
+
+int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
+  if (!ctx || !g) return CSER_EINVAL;
+  if (!aligned(g, 4)) return CSER_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint64_t t = ctx->t + 1;
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 0u, t, static_cast<uint32_t>(ctx->B), ctx->k_step, ctx->mask_step,
+                                 ctx->idx_step, s));
+  cser::StepParams p;
+  p.g = g;
+  p.m = ctx->m;
+  p.x = ctx->x;
+  p.e = ctx->e;
+  p.mask = ctx->mask_step;
+  p.ld = ctx->cfg.ld;
+  p.d = ctx->cfg.d;
+  p.W = ctx->cfg.W;
+  p.block = ctx->cfg.block;
+  p.eta = ctx->cfg.lr;
+  p.beta = ctx->cfg.momentum;
+  bool timed = false;
+  int rc = record_begin(ctx, 0, s, &timed);
+  if (rc != CSER_OK) return rc;
+  CSER_HIP(cser::launch_step(p, ctx->vector_layout && aligned(g, 16), ctx->tuning, s));
+  rc = record_end(ctx, 0, s, timed);
+  if (rc != CSER_OK) return rc;
+  ctx->t = t;
+  if (ctx->cfg.H > 0 && t % ctx->cfg.H == 0) return cser_error_reset(ctx, hip_stream);
+  return CSER_OK;
+}
+
+int cser_destroy(cser_ctx* ctx) {
+  if (!ctx) return CSER_OK;
+  free_device_arrays(ctx);
+  delete ctx;
+  return CSER_OK;
+}
+
+int cser_select_blocks(cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host, uint8_t* mask_host,
+                       uint32_t* k_out) {
+  if (!ctx || (which != 0 && which != 1)) return CSER_EINVAL;
+  const uint32_t k = which == 0 ? ctx->k_step : ctx->k_reset;
+  if (k_out) *k_out = k;
+  if (!ctx->idx_query) {
+    hipError_t err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_query), sizeof(uint32_t) * ctx->B);
+    if (err == hipErrorOutOfMemory) return CSER_ENOMEM;
+    if (err != hipSuccess) return hip_failed(err, "hipMalloc");
+  }
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, static_cast<uint32_t>(which), t, static_cast<uint32_t>(ctx->B), k,
+                                 ctx->mask_query, ctx->idx_query, nullptr));
+  CSER_HIP(hipStreamSynchronize(nullptr));
+  if (mask_host) CSER_HIP(hipMemcpy(mask_host, ctx->mask_query, ctx->B, hipMemcpyDeviceToHost));
+  if (idx_host && k) CSER_HIP(hipMemcpy(idx_host, ctx->idx_query, sizeof(uint32_t) * k, hipMemcpyDeviceToHost));
+  return CSER_OK;
+}
+
+int cser_block_counts(const cser_ctx* ctx, uint64_t* B, uint32_t* k_step, uint32_t* k_reset) {
+  if (!ctx) return CSER_EINVAL;
+  if (B) *B = ctx->B;
+  if (k_step) *k_step = ctx->k_step;
+  if (k_reset) *k_reset = ctx->k_reset;
+  return CSER_OK;
+}
+
+int cser_set_lr(cser_ctx* ctx, float lr) {
+  if (!ctx || !std::isfinite(lr)) return CSER_EINVAL;
+  ctx->cfg.lr = lr;
+  return CSER_OK;
+}
+
+int cser_get_step(const cser_ctx* ctx, uint64_t* t) {
+  if (!ctx || !t) return CSER_EINVAL;
+  *t = ctx->t;
+  return CSER_OK;
+}
+
+int cser_set_step(cser_ctx* ctx, uint64_t t) {
+  if (!ctx) return CSER_EINVAL;
+  ctx->t = t;
+  return CSER_OK;
+}
+
+int cser_profile_enable(cser_ctx* ctx, int on) {
+  if (!ctx) return CSER_EINVAL;
+  ctx->profiling = on != 0;
+  return CSER_OK;
+}
+
+int cser_profile_read(cser_ctx* ctx, int which, double* total_ms, uint64_t* launches) {
+  if (!ctx || (which != 0 && which != 1)) return CSER_EINVAL;
+  Timer& tm = ctx->timers[which];
+  const int rc = drain_timer(tm);
+  if (rc != CSER_OK) return rc;
+  if (total_ms) *total_ms = tm.total_ms;
+  if (launches) *launches = tm.launches;
+  return CSER_OK;
+}
+
+int cser_profile_clear(cser_ctx* ctx) {
+  if (!ctx) return CSER_EINVAL;
+  for (Timer& tm : ctx->timers) {
+    const int rc = drain_timer(tm);
+    if (rc != CSER_OK) return rc;
+    tm.total_ms = 0.0;
+    tm.launches = 0;
+  }
+  return CSER_OK;
+}
+
+int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
+  if (!ctx) return CSER_EINVAL;
+  switch (key) {
+    case 0:
+      if (value < 0 || value > 0x7FFFFFFF) return CSER_EINVAL;
+      ctx->tuning.wg_cap = value;
+      return CSER_OK;
+    case 1:
+      ctx->tuning.nontemporal = value != 0;
+      return CSER_OK;
+    case 2:
+      if (value != 1 && value != 2 && value != 4 && value != 8) return CSER_EINVAL;
+      ctx->tuning.batch = static_cast<int>(value);
+      return CSER_OK;
+    default:
+      return CSER_EINVAL;
+  }
+}
+
+int cser_copy_probe(void* dst, const void* src, uint64_t n_bytes, void* hip_stream) {
+  if (!dst || !src) return CSER_EINVAL;
+  if (!aligned(dst, 16) || !aligned(src, 16) || n_bytes % 16 != 0) return CSER_EALIGN;
+  if (n_bytes / 16 / 256 > 0x7FFFFFFFull) return CSER_ERANGE;
+  CSER_HIP(cser::launch_copy(dst, src, n_bytes, static_cast<hipStream_t>(hip_stream)));
+  return CSER_OK;
+}
+
+const char* cser_strerror(int status) {
+  switch (status) {
+    case CSER_OK: return "ok";
+    case CSER_EINVAL: return "invalid argument";
+    case CSER_EALIGN: return "misaligned pointer or size";
+    case CSER_ENOMEM: return "out of memory";
+    case CSER_EHIP: return "HIP runtime error (see cser_last_hip_error)";
+    case CSER_ERANGE: return "size beyond the supported range";
+    default: return "unknown status";
+  }
+}
+
+const char* cser_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+}  // extern "C"

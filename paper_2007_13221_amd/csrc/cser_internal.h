@@ -1,0 +1,58 @@
+// Internal interface between the C ABI (cser_api.hip) and the kernels (cser_kernels.hip).
+// Host-side launch wrappers only; every wrapper validates nothing (the ABI layer has done it)
+// and returns the hipError_t of its launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cser {
+
+// Everything the fused-step kernels need.  Rows are [W][ld] fp32; e and m may be null
+// (implementation II of Appendix A.4 / Algorithm 2 without momentum).
+struct StepParams {
+  const float* g;
+  float* m;
+  float* x;
+  float* e;
+  const uint8_t* mask;  // B bytes, 1 = block chosen by C_step for this t
+  uint64_t ld;
+  uint64_t d;
+  uint32_t W;
+  uint32_t block;
+  float eta;
+  float beta;
+};
+
+struct ResetParams {
+  float* x;
+  float* e;             // null: implementation II (average x itself)
+  const uint32_t* idx;  // k chosen block ids
+  uint64_t ld;
+  uint64_t d;
+  uint32_t W;
+  uint32_t block;
+  uint32_t k;
+};
+
+struct Tuning {
+  int64_t wg_cap = 0;   // 0: one 4-column group per lane; > 0: at most this many workgroups
+  int nontemporal = 1;
+  int batch = 4;        // workers whose loads are issued together
+};
+
+// GRBS block selector (Definition 2): mask[b] = 1 and idx[pi^-1(b)] = b for the k chosen blocks.
+hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t, uint32_t B, uint32_t k,
+                           uint8_t* mask, uint32_t* idx, hipStream_t s);
+
+// Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d).  `vectorised` requires ld and
+// block multiples of 4 and 16-byte aligned rows.
+hipError_t launch_step(const StepParams& p, bool vectorised, const Tuning& tune, hipStream_t s);
+
+// Error reset on the chosen blocks (idx: the k chosen ids; mask: the same choice as B bytes).
+hipError_t launch_reset(const ResetParams& p, const uint8_t* mask, bool vectorised, hipStream_t s);
+
+hipError_t launch_fill_zero(float* ptr, uint64_t n, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, uint64_t n_bytes, hipStream_t s);
+
+}  // namespace cser

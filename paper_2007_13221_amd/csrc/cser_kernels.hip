@@ -1,0 +1,411 @@
+// HIP kernels of the CSER optimizer update for gfx950 (MI355X), and their launch wrappers.
+//
+//   grbs_select_kernel   the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3)
+//   cser_step_kernel     Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass
+//   cser_reset_kernel    the error-reset branch of Algorithm 3 (PSync(e, C_reset) and the x correction)
+//
+// The update is a pure stream over HBM (about 6 flops per 28 bytes), so there is no matrix-core
+// work here.  Each lane owns 4 consecutive columns (one 128-bit access per row and array) and
+// walks the worker axis itself: the W-way sum PSync needs is then a private, fixed-order chain of
+// adds in registers -- no LDS, no cross-lane traffic, and the same order as a sequential
+// evaluation.  A wavefront therefore touches 1 KiB contiguous per row and array, and loads of
+// several workers are issued before the first use to keep many requests in flight.
+//
+// Build with -ffp-contract=off: every fused multiply-add below is written out, nothing else fuses.
+
+#include "cser_internal.h"
+
+namespace cser {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------
+// V consecutive fp32 values (V = 4: one 128-bit access; V = 1: the unaligned fallback).
+// ------------------------------------------------------------------------------------------
+template <int V>
+struct Pack {
+  float v[V];
+};
+
+template <int V, bool NT>
+__device__ __forceinline__ Pack<V> load_pack(const float* p) {
+  Pack<V> r;
+  if constexpr (V == 4) {
+    f4 t;
+    if constexpr (NT) t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    else t = *reinterpret_cast<const f4*>(p);
+    r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+  } else {
+    if constexpr (NT) r.v[0] = __builtin_nontemporal_load(p);
+    else r.v[0] = *p;
+  }
+  return r;
+}
+
+template <int V, bool NT>
+__device__ __forceinline__ void store_pack(float* p, const Pack<V>& r) {
+  if constexpr (V == 4) {
+    f4 t;
+    t.x = r.v[0]; t.y = r.v[1]; t.z = r.v[2]; t.w = r.v[3];
+    if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<f4*>(p));
+    else *reinterpret_cast<f4*>(p) = t;
+  } else {
+    if constexpr (NT) __builtin_nontemporal_store(r.v[0], p);
+    else *p = r.v[0];
+  }
+}
+
+// Get_p (Appendix A.4): m <- beta m + g, p <- eta (beta m + g); without a momentum buffer
+// (beta = 0, Algorithm 2) p <- eta g.
+template <int V, bool HAS_M>
+__device__ __forceinline__ Pack<V> local_update(float eta, float beta, const Pack<V>& g, Pack<V>& m) {
+  Pack<V> p;
+#pragma unroll
+  for (int c = 0; c < V; ++c) {
+    if constexpr (HAS_M) {
+      m.v[c] = __fmaf_rn(beta, m.v[c], g.v[c]);
+      p.v[c] = eta * __fmaf_rn(beta, m.v[c], g.v[c]);
+    } else {
+      p.v[c] = eta * g.v[c];
+    }
+  }
+  return p;
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused step.  For the V columns starting at `col`:
+//   block not chosen by C_step:  C(p_i) = 0 on every worker, so the mean is 0, p'_i = r_i = p_i:
+//                                x_i -= p_i, e_i -= p_i                       (28 B per element)
+//   block chosen:                r_i = 0, p'_i = mean_j p_j:  x_i -= pbar, e_i untouched (20 B)
+// U workers are processed per batch: all their loads are issued before any arithmetic.
+// ------------------------------------------------------------------------------------------
+template <int V, int U, bool NT, bool HAS_E, bool HAS_M>
+__device__ __forceinline__ void step_local_batch(const StepParams& a, uint64_t col, uint32_t i0) {
+  Pack<V> g[U], m[U], x[U], e[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint64_t off = static_cast<uint64_t>(i0 + u) * a.ld + col;
+    g[u] = load_pack<V, NT>(a.g + off);
+    if constexpr (HAS_M) m[u] = load_pack<V, NT>(a.m + off);
+    x[u] = load_pack<V, NT>(a.x + off);
+    if constexpr (HAS_E) e[u] = load_pack<V, NT>(a.e + off);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint64_t off = static_cast<uint64_t>(i0 + u) * a.ld + col;
+    const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g[u], m[u]);
+#pragma unroll
+    for (int c = 0; c < V; ++c) {
+      x[u].v[c] = x[u].v[c] - p.v[c];
+      if constexpr (HAS_E) e[u].v[c] = e[u].v[c] - p.v[c];
+    }
+    if constexpr (HAS_M) store_pack<V, NT>(a.m + off, m[u]);
+    store_pack<V, NT>(a.x + off, x[u]);
+    if constexpr (HAS_E) store_pack<V, NT>(a.e + off, e[u]);
+  }
+}
+
+template <int V, int U, bool NT, bool HAS_M>
+__device__ __forceinline__ void step_sum_batch(const StepParams& a, uint64_t col, uint32_t i0, Pack<V>& sum) {
+  Pack<V> g[U], m[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint64_t off = static_cast<uint64_t>(i0 + u) * a.ld + col;
+    g[u] = load_pack<V, NT>(a.g + off);
+    if constexpr (HAS_M) m[u] = load_pack<V, NT>(a.m + off);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint64_t off = static_cast<uint64_t>(i0 + u) * a.ld + col;
+    const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g[u], m[u]);
+    if constexpr (HAS_M) store_pack<V, NT>(a.m + off, m[u]);
+#pragma unroll
+    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + p.v[c];   // workers in order i = 0, 1, ...
+  }
+}
+
+template <int V, int U, bool NT>
+__device__ __forceinline__ void step_apply_mean_batch(const StepParams& a, uint64_t col, uint32_t i0,
+                                                      const Pack<V>& pbar) {
+  Pack<V> x[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) x[u] = load_pack<V, NT>(a.x + static_cast<uint64_t>(i0 + u) * a.ld + col);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int c = 0; c < V; ++c) x[u].v[c] = x[u].v[c] - pbar.v[c];
+    store_pack<V, NT>(a.x + static_cast<uint64_t>(i0 + u) * a.ld + col, x[u]);
+  }
+}
+
+template <int V, int U, bool NT, bool HAS_E, bool HAS_M>
+__device__ __forceinline__ void step_columns(const StepParams& a, uint64_t col, bool chosen) {
+  if (!chosen) {
+    uint32_t i = 0;
+    for (; i + U <= a.W; i += U) step_local_batch<V, U, NT, HAS_E, HAS_M>(a, col, i);
+    for (; i < a.W; ++i) step_local_batch<V, 1, NT, HAS_E, HAS_M>(a, col, i);
+  } else {
+    Pack<V> sum;
+#pragma unroll
+    for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
+    uint32_t i = 0;
+    for (; i + U <= a.W; i += U) step_sum_batch<V, U, NT, HAS_M>(a, col, i, sum);
+    for (; i < a.W; ++i) step_sum_batch<V, 1, NT, HAS_M>(a, col, i, sum);
+    const float n = static_cast<float>(a.W);
+    Pack<V> pbar;
+#pragma unroll
+    for (int c = 0; c < V; ++c) pbar.v[c] = sum.v[c] / n;
+    i = 0;
+    for (; i + U <= a.W; i += U) step_apply_mean_batch<V, U, NT>(a, col, i, pbar);
+    for (; i < a.W; ++i) step_apply_mean_batch<V, 1, NT>(a, col, i, pbar);
+  }
+}
+
+// Columns [col_begin, col_end) in groups of V; group q covers col_begin + q*V ...  `groups` is
+// the number of whole groups.  groups_per_block = block / V (vector path: block % 4 == 0 and
+// col_begin % block == 0, so a group never straddles two blocks).
+template <int V, int U, bool NT, bool HAS_E, bool HAS_M>
+__global__ __launch_bounds__(256) void cser_step_kernel(StepParams a, uint64_t col_begin, uint32_t groups) {
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; q < groups; q += stride) {
+    const uint64_t col = col_begin + q * V;
+    uint32_t b;
+    if constexpr (V == 4) b = static_cast<uint32_t>(q) / (a.block / 4u);   // vector path starts at column 0
+    else b = static_cast<uint32_t>(col / a.block);
+    step_columns<V, U, NT, HAS_E, HAS_M>(a, col, a.mask[b] != 0);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Error reset (Algorithm 3, t mod H = 0) on the V columns at `col` of a chosen block:
+//   ebar = (e_0 + e_1 + ... + e_{W-1}) / W ;  x_i <- (x_i - e_i) + ebar ;  e_i <- +0
+// Implementation II (no e): x_i <- (x_0 + ... + x_{W-1}) / W.
+// The second pass re-reads e_i; the lines were just fetched by this lane, so they come from L2.
+// ------------------------------------------------------------------------------------------
+template <int V, bool HAS_E>
+__device__ __forceinline__ void reset_columns(const ResetParams& a, uint64_t col) {
+  float* src = HAS_E ? a.e : a.x;
+  Pack<V> sum;
+#pragma unroll
+  for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
+  for (uint32_t i = 0; i < a.W; ++i) {
+    const Pack<V> v = load_pack<V, false>(src + static_cast<uint64_t>(i) * a.ld + col);
+#pragma unroll
+    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + v.v[c];
+  }
+  const float n = static_cast<float>(a.W);
+  Pack<V> mean, zero;
+#pragma unroll
+  for (int c = 0; c < V; ++c) {
+    mean.v[c] = sum.v[c] / n;
+    zero.v[c] = 0.0f;
+  }
+  for (uint32_t i = 0; i < a.W; ++i) {
+    const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
+    if constexpr (HAS_E) {
+      const Pack<V> e = load_pack<V, false>(a.e + off);
+      Pack<V> x = load_pack<V, false>(a.x + off);
+#pragma unroll
+      for (int c = 0; c < V; ++c) x.v[c] = (x.v[c] - e.v[c]) + mean.v[c];
+      store_pack<V, false>(a.x + off, x);
+      store_pack<V, false>(a.e + off, zero);
+    } else {
+      store_pack<V, false>(a.x + off, mean);
+    }
+  }
+}
+
+// Vector path: one lane per 4-column group of a chosen block; the block list comes from idx.
+template <bool HAS_E>
+__global__ __launch_bounds__(256) void cser_reset_kernel(ResetParams a, uint32_t groups_per_block,
+                                                          uint64_t total_groups) {
+  const uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (q >= total_groups) return;
+  const uint32_t j = static_cast<uint32_t>(q / groups_per_block);
+  const uint32_t within = static_cast<uint32_t>(q - static_cast<uint64_t>(j) * groups_per_block);
+  const uint64_t col = static_cast<uint64_t>(a.idx[j]) * a.block + static_cast<uint64_t>(within) * 4;
+  if (col + 4 > a.d) return;   // ragged last block; a trailing partial group goes to the scalar kernel
+  reset_columns<4, HAS_E>(a, col);
+}
+
+// Element-wise path over columns [col_begin, col_end): uses the mask, any alignment.
+template <bool HAS_E>
+__global__ __launch_bounds__(256) void cser_reset_scalar_kernel(ResetParams a, const uint8_t* mask,
+                                                                 uint64_t col_begin, uint64_t col_end) {
+  const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (col >= col_end) return;
+  if (mask[col / a.block] == 0) return;
+  reset_columns<1, HAS_E>(a, col);
+}
+
+// ------------------------------------------------------------------------------------------
+// Block selector.  All workers must pick the same k of the B blocks from a shared seed
+// (Definition 2).  The choice is {pi(0), ..., pi(k-1)} for a keyed permutation pi of [0, B):
+// block b is chosen iff pi^-1(b) < k, which every block can decide for itself -- no sort, no
+// atomics, one thread per block.
+//
+// pi: 8-round balanced Feistel network on 2h bits (2^(2h) >= B), round function = low h bits of
+// word 0 of Philox-4x32-10 (Salmon et al., SC'11) keyed by the seed with counter
+// (half, stream*65536 + round, t_lo, t_hi); values >= B are walked through the network again
+// (cycle walking).  This kernel evaluates the inverse.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t philox_first_word(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                      uint32_t k0, uint32_t k1) {
+  constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;
+  constexpr uint32_t kWeylA = 0x9E3779B9u, kWeylB = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hiA = __umulhi(kMulA, c0), loA = kMulA * c0;
+    const uint32_t hiB = __umulhi(kMulB, c2), loB = kMulB * c2;
+    c0 = hiB ^ c1 ^ k0;
+    c1 = loB;
+    c2 = hiA ^ c3 ^ k1;
+    c3 = loA;
+    k0 += kWeylA;
+    k1 += kWeylB;
+  }
+  return c0;
+}
+
+__global__ __launch_bounds__(256) void grbs_select_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
+                                                           uint32_t t_lo, uint32_t t_hi, uint32_t B, uint32_t k,
+                                                           uint32_t half_bits, uint8_t* mask, uint32_t* idx) {
+  const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const uint32_t half_mask = (1u << half_bits) - 1u;
+  // The network is a bijection of the 2^(2h) values, so the walk from b returns to b after at most
+  // 2^(2h) applications and passes a value < B no later than that: the bound below is never the
+  // reason the loop ends, it only makes termination independent of that argument.
+  const uint64_t domain = 1ull << (2 * half_bits);
+  uint32_t v = b;
+  for (uint64_t walk = 0; walk < domain; ++walk) {
+    uint32_t hi = (v >> half_bits) & half_mask;
+    uint32_t lo = v & half_mask;
+    // undo rounds 7..0 of (L, R) -> (R, L ^ F(round, R)):  given (hi, lo) = (R, L ^ F), recover (L, R)
+    for (int round = 7; round >= 0; --round) {
+      const uint32_t f = philox_first_word(hi, stream_id * 65536u + static_cast<uint32_t>(round), t_lo, t_hi,
+                                           seed_lo, seed_hi) & half_mask;
+      const uint32_t prev_left = lo ^ f;
+      lo = hi;
+      hi = prev_left;
+    }
+    v = (hi << half_bits) | lo;
+    if (v < B) break;
+  }
+  const bool chosen = v < k;
+  mask[b] = chosen ? 1 : 0;
+  if (chosen) idx[v] = b;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* p, uint64_t n) {
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.0f;
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(f4* __restrict__ dst, const f4* __restrict__ src, uint64_t n16) {
+  const uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+// ---------------------------------------------------------------- launch helpers
+uint32_t half_bits_for(uint32_t B) {
+  uint32_t bits = 0;
+  while ((1ull << bits) < B) ++bits;
+  if (bits < 2) bits = 2;
+  return (bits + 1) / 2;
+}
+
+template <int V, int U, bool NT>
+hipError_t launch_step_flags(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, hipStream_t s) {
+  const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
+  if (has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, true>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
+  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, false>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
+  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, true>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
+  else hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, false>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
+  return hipGetLastError();
+}
+
+template <int V, bool NT>
+hipError_t launch_step_batch(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, int batch,
+                             hipStream_t s) {
+  switch (batch) {
+    case 1: return launch_step_flags<V, 1, NT>(p, col_begin, groups, grid, s);
+    case 2: return launch_step_flags<V, 2, NT>(p, col_begin, groups, grid, s);
+    case 8: return launch_step_flags<V, 8, NT>(p, col_begin, groups, grid, s);
+    default: return launch_step_flags<V, 4, NT>(p, col_begin, groups, grid, s);
+  }
+}
+
+template <int V>
+hipError_t launch_step_range(const StepParams& p, uint64_t col_begin, uint64_t col_end, const Tuning& tune,
+                             hipStream_t s) {
+  if (col_end <= col_begin) return hipSuccess;
+  const uint64_t groups64 = (col_end - col_begin) / V;
+  if (groups64 == 0) return hipSuccess;
+  const uint32_t groups = static_cast<uint32_t>(groups64);
+  uint64_t grid = (groups64 + 255) / 256;
+  if (tune.wg_cap > 0 && grid > static_cast<uint64_t>(tune.wg_cap)) grid = static_cast<uint64_t>(tune.wg_cap);
+  if (tune.nontemporal) return launch_step_batch<V, true>(p, col_begin, groups, static_cast<uint32_t>(grid), tune.batch, s);
+  return launch_step_batch<V, false>(p, col_begin, groups, static_cast<uint32_t>(grid), tune.batch, s);
+}
+
+}  // namespace
+
+hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t, uint32_t B, uint32_t k, uint8_t* mask,
+                           uint32_t* idx, hipStream_t s) {
+  const uint32_t grid = (B + 255u) / 256u;
+  hipLaunchKernelGGL(grbs_select_kernel, dim3(grid), dim3(256), 0, s, static_cast<uint32_t>(seed),
+                     static_cast<uint32_t>(seed >> 32), stream_id, static_cast<uint32_t>(t),
+                     static_cast<uint32_t>(t >> 32), B, k, half_bits_for(B), mask, idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_step(const StepParams& p, bool vectorised, const Tuning& tune, hipStream_t s) {
+  if (!vectorised) return launch_step_range<1>(p, 0, p.d, tune, s);
+  const uint64_t d4 = p.d & ~3ull;
+  hipError_t err = launch_step_range<4>(p, 0, d4, tune, s);
+  if (err != hipSuccess) return err;
+  return launch_step_range<1>(p, d4, p.d, tune, s);   // at most 3 trailing columns
+}
+
+hipError_t launch_reset(const ResetParams& p, const uint8_t* mask, bool vectorised, hipStream_t s) {
+  if (p.k == 0) return hipSuccess;
+  const bool has_e = p.e != nullptr;
+  uint64_t scalar_begin = 0;
+  if (vectorised) {
+    const uint32_t gpb = p.block / 4;
+    const uint64_t total = static_cast<uint64_t>(p.k) * gpb;
+    const uint32_t grid = static_cast<uint32_t>((total + 255) / 256);
+    if (has_e) hipLaunchKernelGGL(cser_reset_kernel<true>, dim3(grid), dim3(256), 0, s, p, gpb, total);
+    else hipLaunchKernelGGL(cser_reset_kernel<false>, dim3(grid), dim3(256), 0, s, p, gpb, total);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    scalar_begin = p.d & ~3ull;
+  }
+  if (scalar_begin >= p.d) return hipSuccess;
+  const uint64_t n = p.d - scalar_begin;
+  const uint32_t grid = static_cast<uint32_t>((n + 255) / 256);
+  if (has_e) hipLaunchKernelGGL(cser_reset_scalar_kernel<true>, dim3(grid), dim3(256), 0, s, p, mask, scalar_begin, p.d);
+  else hipLaunchKernelGGL(cser_reset_scalar_kernel<false>, dim3(grid), dim3(256), 0, s, p, mask, scalar_begin, p.d);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float* ptr, uint64_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  uint64_t grid = (n + 255) / 256;
+  if (grid > 65536) grid = 65536;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(static_cast<uint32_t>(grid)), dim3(256), 0, s, ptr, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, uint64_t n_bytes, hipStream_t s) {
+  const uint64_t n16 = n_bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  const uint64_t grid = (n16 + 255) / 256;
+  hipLaunchKernelGGL(copy_kernel, dim3(static_cast<uint32_t>(grid)), dim3(256), 0, s, static_cast<f4*>(dst),
+                     static_cast<const f4*>(src), n16);
+  return hipGetLastError();
+}
+
+}  // namespace cser

@@ -1,0 +1,64 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2007_13221_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "cser.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cser_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert "cser_create" in names and "cser_step" in names and "cser_error_reset" in names and "cser_destroy" in names
+    lib = ctypes.CDLL(B.LIBRARY)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(B.EXPORTS) == names          # the binding covers the whole header, nothing more
+
+
+def test_config_struct_layout_matches_the_header():
+    assert ctypes.sizeof(B.cser_config) == 56
+    assert B.cser_config.seed.offset == 48 and B.cser_config.lr.offset == 36
+
+
+def test_strerror_and_null_destroy():
+    assert B.cser_strerror(0) == "ok"
+    assert "invalid" in B.cser_strerror(B.CSER_EINVAL)
+    assert B._lib().cser_destroy(None) == B.CSER_OK
+
+
+@pytest.mark.parametrize("change,status", [
+    (dict(d=0), B.CSER_EINVAL), (dict(W=0), B.CSER_EINVAL), (dict(block=0), B.CSER_EINVAL),
+    (dict(ld=10), B.CSER_EINVAL), (dict(R_reset=0), B.CSER_EINVAL), (dict(momentum=1.0), B.CSER_EINVAL),
+    (dict(momentum=-0.1), B.CSER_EINVAL), (dict(lr=float("nan")), B.CSER_EINVAL),
+    (dict(d=2**40, ld=2**40, block=1), B.CSER_ERANGE),
+])
+def test_create_rejects_bad_configs_without_a_device(change, status):
+    kw = dict(d=64, W=2, block=8, R_step=2, R_reset=2, H=2, lr=0.1, momentum=0.9, seed=1, ld=64)
+    kw.update(change)
+    cfg = B.make_config(**kw)
+    out = ctypes.c_void_p(123)
+    fake = 0x1000   # never dereferenced: validation fails first
+    rc = B._lib().cser_create(ctypes.byref(cfg), fake, fake, fake, None, ctypes.byref(out))
+    assert rc == status and out.value is None
+
+
+def test_create_rejects_null_and_misaligned_pointers():
+    cfg = B.make_config(64, 2, 8, 2, 2, 2, 0.1, 0.9, 1)
+    out = ctypes.c_void_p()
+    assert B._lib().cser_create(ctypes.byref(cfg), None, 0x1000, 0x1000, None, ctypes.byref(out)) == B.CSER_EINVAL
+    assert B._lib().cser_create(ctypes.byref(cfg), 0x1002, 0x1000, 0x1000, None, ctypes.byref(out)) == B.CSER_EALIGN
+    assert B._lib().cser_create(ctypes.byref(cfg), 0x1000, 0x1000, None, None, ctypes.byref(out)) == B.CSER_EINVAL  # no m with beta > 0
+    assert B._lib().cser_create(None, 0x1000, 0x1000, 0x1000, None, ctypes.byref(out)) == B.CSER_EINVAL
+    assert B._lib().cser_step(None, 0x1000, None) == B.CSER_EINVAL
+    assert B._lib().cser_error_reset(None, None) == B.CSER_EINVAL

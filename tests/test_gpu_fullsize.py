@@ -1,0 +1,111 @@
+"""Full-size GPU parity in the launch configuration bench.py times.
+
+At d = 25.6 M (and 335 M) the oracle cannot run the whole vector in test time, but every block
+evolves independently given the global block choice, so the oracle simulates sampled blocks
+(first, last with its ragged tail, blocks chosen by C_step and by C_reset at known iterations, and
+random ones) bit for bit, while properties that hold at any size cover every element: Lemma 1
+(x_i - e_i common to all workers) and the mean-model identity from the proofs
+(xbar_t = xbar_{t-1} - mean_i p_{i,t}), evaluated in float64 with torch as an independent check.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as R
+from paper_2007_13221_amd import binding as B
+from paper_2007_13221_amd import inputs as I
+from tests.test_gpu_parity import assert_states_close
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_blocks(wl, steps, rng, extra_reset_t=None):
+    Bn = wl.B
+    ks, kr = R.blocks_kept(Bn, wl.R_step), R.blocks_kept(Bn, wl.R_reset)
+    blocks = {0, 1 % Bn, Bn - 1, max(Bn - 2, 0)}
+    for t in sorted({1, 2, steps}):
+        blocks.update(int(b) for b in R.select_blocks(wl.seed, 0, t, Bn, ks)[0][:2])
+    reset_ts = [t for t in range(1, steps + 1) if wl.H and t % wl.H == 0]
+    if extra_reset_t:
+        reset_ts.append(extra_reset_t)
+    for t in reset_ts[:2] + reset_ts[-1:]:
+        blocks.update(int(b) for b in R.select_blocks(wl.seed, 1, t, Bn, kr)[0][:3])
+    blocks.update(int(b) for b in rng.integers(0, Bn, size=4))
+    return sorted(blocks)
+
+
+def run_sliced(wl, steps, check_mean_model=True, forced_reset=False):
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(wl.seed + 1000)
+    ld = wl.ld
+    x = I.initial_model(wl, dev)
+    x0_row = x[0, :wl.d].clone()
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=ld)
+    opt = B.CSER(cfg, x)
+    blocks = sample_blocks(wl, steps, rng, extra_reset_t=steps if forced_reset else None)
+    oracles = []
+    for b in blocks:
+        c0, c1 = b * wl.block, min(wl.d, (b + 1) * wl.block)
+        oracles.append((c0, c1, R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum,
+                                             wl.seed, x0_row[c0:c1].cpu().numpy(), b0=b, b1=b + 1)))
+    g = torch.zeros(wl.W, ld, device=dev, dtype=torch.float32)
+    if check_mean_model:
+        m64 = torch.zeros(wl.W, wl.d, device=dev, dtype=torch.float64)
+        xbar = x0_row.double()
+        beta, eta = float(np.float32(wl.momentum)), float(np.float32(wl.lr))
+    for t in range(1, steps + 1):
+        I.gradient(wl, t, dev, out=g)
+        opt.step(g)
+        for c0, c1, o in oracles:
+            o.step(g[:, c0:c1].cpu().numpy())
+        if check_mean_model:
+            g64 = g[:, :wl.d].double()
+            m64.mul_(beta).add_(g64)
+            xbar -= (eta * (beta * m64 + g64)).mean(dim=0)
+            del g64
+    if forced_reset:
+        opt.error_reset()
+        for _, _, o in oracles:
+            o.error_reset()
+    torch.cuda.synchronize()
+
+    not_identical = 0
+    for c0, c1, o in oracles:
+        not_identical += assert_states_close("x", opt.x[:, c0:c1].cpu().numpy(), o.x)
+        not_identical += assert_states_close("e", opt.e[:, c0:c1].cpu().numpy(), o.e)
+        not_identical += assert_states_close("m", opt.m[:, c0:c1].cpu().numpy(), o.m)
+    assert not_identical == 0, f"{not_identical} sampled elements not bit-identical"
+
+    # Lemma 1 on every column: x_i - e_i is the same for all workers, up to fp32 rounding of the
+    # accumulated updates (each step rounds x and e separately)
+    z = opt.x[:, :wl.d].double() - opt.e[:, :wl.d].double()
+    spread = (z - z[0]).abs().max().item()
+    scale = max(1.0, opt.x.abs().max().item())
+    assert spread <= steps * 2.0 ** -22 * scale, spread
+    del z
+    if check_mean_model:
+        got = opt.x[:, :wl.d].double().mean(dim=0)
+        err = (got - xbar).abs().max().item()
+        assert err <= steps * 2.0 ** -22 * scale, err
+    # padding columns were never touched
+    if ld > wl.d:
+        assert not opt.x[:, wl.d:].any() and not opt.e[:, wl.d:].any() and not opt.m[:, wl.d:].any()
+    opt.close()
+
+
+def test_large_cnn_full_size_34_steps_with_reset():
+    run_sliced(I.WORKLOADS["large_cnn"], 34)
+
+
+@pytest.mark.parametrize("R_step,block,H", [(2, 64, 4), (1024, 4096, 4), (8, 256, 4), (32, 1024, 4)])
+def test_compression_sweep_corners_full_size(R_step, block, H):
+    wl = replace(I.WORKLOADS["large_cnn"], name="sweep", R_step=R_step, block=block, R_reset=16, H=H, seed=3)
+    run_sliced(wl, 6, check_mean_model=False)
+
+
+def test_transformer_sized_stress_with_forced_reset():
+    # 20 steps are fewer than H = 64, so the reset is forced once at the end, as the workload prescribes
+    wl = I.WORKLOADS["transformer"]
+    run_sliced(wl, 6, check_mean_model=False, forced_reset=True)

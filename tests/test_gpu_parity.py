@@ -1,0 +1,283 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Block indices and masks must be bit-exact; fp32 states must satisfy
+|gpu - oracle| <= 1e-7 + 1e-6 |oracle| (the stated bar); with the shared arithmetic contract
+(written-out fused multiply-adds, in-order worker sum, true division) the two are in fact expected
+to agree bit for bit, which the tests also record.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as R
+from paper_2007_13221_amd import binding as B
+from paper_2007_13221_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+ABS_TOL, REL_TOL = 1e-7, 1e-6
+
+
+def assert_states_close(name, got, want):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (name, got.shape, want.shape)
+    err = np.abs(got - want)
+    bound = ABS_TOL + REL_TOL * np.abs(want)
+    bad = err > bound
+    assert not bad.any(), f"{name}: {int(bad.sum())} of {bad.size} beyond tolerance, worst {err.max():.3e}"
+    return int((got != want).sum())
+
+
+def run_pair(wl, steps, ld=None, with_error=True, with_momentum=True, tuning=None, lr_schedule=None,
+             x_offset=0, check_every=None):
+    """Run `steps` iterations on the GPU and in the fp32 oracle on identical inputs; compare at the end
+    (and every `check_every` steps).  Returns (gpu object, oracle, number of elements not bit-identical)."""
+    dev = torch.device("cuda:0")
+    ld = wl.ld if ld is None else ld
+    x = I.initial_model(wl, dev, ld=ld)
+    if x_offset:   # deliberately misaligned rows: a view into a larger buffer
+        big = torch.zeros(wl.W * ld + 8, device=dev, dtype=torch.float32)
+        view = big[x_offset:x_offset + wl.W * ld].view(wl.W, ld)
+        view.copy_(x)
+        x = view
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=ld)
+    e = torch.zeros_like(x) if with_error else None
+    m = torch.zeros_like(x) if with_momentum else None
+    if x_offset:
+        ebig = torch.zeros(wl.W * ld + 8, device=dev, dtype=torch.float32)
+        mbig = torch.zeros(wl.W * ld + 8, device=dev, dtype=torch.float32)
+        e = ebig[x_offset:x_offset + wl.W * ld].view(wl.W, ld) if with_error else None
+        m = mbig[x_offset:x_offset + wl.W * ld].view(wl.W, ld) if with_momentum else None
+    ctx = B.cser_create(cfg, x, e, m)
+    for key, value in (tuning or {}).items():
+        B.cser_set_tuning(ctx, key, value)
+    x0 = I.initial_model_row(wl, dev).cpu().numpy()
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum if with_momentum else 0.0,
+                     wl.seed, x0, dtype=np.float32, with_error=with_error)
+    g = torch.zeros(wl.W, ld, device=dev, dtype=torch.float32)
+    if x_offset:
+        gbig = torch.zeros(wl.W * ld + 8, device=dev, dtype=torch.float32)
+        g = gbig[x_offset:x_offset + wl.W * ld].view(wl.W, ld)
+    diff = 0
+
+    def compare():
+        torch.cuda.synchronize()
+        n = assert_states_close("x", x[:, :wl.d].cpu().numpy(), o.x)
+        if with_error:
+            n += assert_states_close("e", e[:, :wl.d].cpu().numpy(), o.e)
+        if with_momentum:
+            n += assert_states_close("m", m[:, :wl.d].cpu().numpy(), o.m)
+        return n
+
+    for t in range(1, steps + 1):
+        if lr_schedule is not None:
+            B.cser_set_lr(ctx, lr_schedule(t))
+            o.set_lr(lr_schedule(t))
+        I.gradient(wl, t, dev, ld=ld, out=g)
+        B.cser_step(ctx, g)
+        o.step(g[:, :wl.d].cpu().numpy())
+        if check_every and t % check_every == 0:
+            diff += compare()
+    diff += compare()
+    assert B.cser_get_step(ctx) == steps == o.t
+    B.cser_destroy(ctx)
+    return diff
+
+
+# ---------------------------------------------------------------------------- selector
+@pytest.mark.parametrize("d,block,R_step,R_reset", [
+    (65536, 256, 8, 4), (855770, 512, 32, 8), (25557032, 1024, 256, 16), (25557032, 64, 2, 16),
+    (25557032, 4096, 1024, 16), (335000000, 4096, 512, 32), (100, 7, 3, 1), (5, 8, 1, 1), (64, 1, 0, 2), (3, 1, 2, 3),
+])
+def test_selector_indices_and_masks_are_bit_exact(d, block, R_step, R_reset):
+    dev = torch.device("cuda:0")
+    x = torch.zeros(1, 64, device=dev)   # never touched: only the selector runs
+    cfg = B.make_config(d, 1, block, R_step, R_reset, 1, 0.1, 0.0, 0xDEADBEEF12345, ld=d)
+    ctx = B.cser_create(cfg, x, None, None)   # no e, no m: nothing is filled, x is a dummy
+    Bn, ks, kr = B.cser_block_counts(ctx)
+    assert Bn == -(-d // block) and ks == R.blocks_kept(Bn, R_step) and kr == R.blocks_kept(Bn, R_reset)
+    for which, k in ((0, ks), (1, kr)):
+        for t in (0, 1, 2, 31, 2**32 + 5, 2**63 + 11):
+            idx, mask = B.cser_select_blocks(ctx, which, t)
+            ridx, rmask = R.select_blocks(cfg.seed, which, t, Bn, k)
+            assert np.array_equal(mask, rmask), (which, t)
+            assert np.array_equal(idx, ridx), (which, t)
+    B.cser_destroy(ctx)
+
+
+# ---------------------------------------------------------------------------- named workloads
+def test_tiny_workload_100_steps():
+    wl = I.WORKLOADS["tiny"]
+    diff = run_pair(wl, 100, check_every=20)
+    assert diff == 0, f"{diff} elements not bit-identical"
+
+
+def test_small_cnn_workload_200_steps_ragged_tail():
+    wl = I.WORKLOADS["small_cnn"]          # d = 855,770: last block has 218 columns, d % 4 == 2
+    assert wl.d % 4 == 2 and wl.d % wl.block == 218
+    diff = run_pair(wl, 200, check_every=100)
+    assert diff == 0, f"{diff} elements not bit-identical"
+
+
+# ---------------------------------------------------------------------------- layouts and degenerate cases
+def _wl(**kw):
+    base = dict(name="case", d=5000, W=4, block=64, R_step=4, R_reset=2, H=3, lr=0.1, momentum=0.9,
+                x_var=1e-2, g_var=1e-2, seed=11, steps=12)
+    base.update(kw)
+    return I.Workload(**base)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),                                   # plain
+    dict(W=1),                                # one worker: plain SGD
+    dict(W=3), dict(W=5), dict(W=9),          # division by a non power of two; batch remainder
+    dict(W=16),
+    dict(R_step=0),                           # C_step keeps nothing (CSER-PL)
+    dict(R_step=0, H=1),                      # CSEA
+    dict(R_step=1),                           # identity: fully synchronous
+    dict(R_reset=1),                          # full reset
+    dict(H=0),                                # never reset
+    dict(H=1),
+    dict(d=40, block=64),                     # d smaller than one block
+    dict(d=1, block=1, W=2),
+    dict(d=4099, block=4),                    # smallest vector block, ragged d
+    dict(d=4099, block=1),                    # element-wise blocks
+    dict(d=4099, block=6),                    # block not a multiple of 4: element-wise kernels
+    dict(d=70000, block=4096, R_step=2),      # block larger than a workgroup's columns
+    dict(momentum=0.0),
+    dict(lr=0.0),
+])
+def test_edge_cases_match_bit_for_bit(kw):
+    wl = _wl(**kw)
+    assert run_pair(wl, wl.steps) == 0
+
+
+def test_row_stride_equal_to_unaligned_d_uses_elementwise_kernels():
+    wl = _wl(d=4099)
+    assert run_pair(wl, 12, ld=4099) == 0
+
+
+def test_misaligned_base_pointers():
+    wl = _wl(d=4096)
+    assert run_pair(wl, 12, ld=4096, x_offset=1) == 0
+    assert run_pair(wl, 12, ld=4096, x_offset=4) == 0
+
+
+def test_implementation_two_without_residual_buffer():
+    wl = _wl(d=20000, W=8, steps=16)
+    assert run_pair(wl, 16, with_error=False) == 0
+
+
+def test_no_momentum_buffer_is_algorithm_2():
+    wl = _wl(d=20000, W=8, momentum=0.0)
+    assert run_pair(wl, 12, with_momentum=False) == 0
+    assert run_pair(wl, 12, with_momentum=False, with_error=False) == 0
+
+
+@pytest.mark.parametrize("tuning", [{0: 1}, {0: 7}, {1: 0}, {2: 1}, {2: 2}, {2: 8}, {0: 3, 1: 0, 2: 8}])
+def test_results_do_not_depend_on_launch_shape(tuning):
+    wl = _wl(d=30000, W=8, steps=8)
+    assert run_pair(wl, 8, tuning=tuning) == 0
+
+
+def test_learning_rate_schedule():
+    wl = _wl()
+    assert run_pair(wl, 12, lr_schedule=lambda t: 0.1 / t) == 0
+
+
+def test_forced_reset_and_resume_from_checkpoint():
+    dev = torch.device("cuda:0")
+    wl = _wl(d=9000, W=4, H=4)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+
+    def run(n0, n1):
+        x = I.initial_model(wl, dev)
+        opt = B.CSER(cfg, x)
+        for t in range(1, n0 + 1):
+            opt.step(I.gradient(wl, t, dev))
+        if n1:
+            # "checkpoint": copy the state, build a fresh context on the copies, restore t
+            x2, e2, m2 = opt.x.clone(), opt.e.clone(), opt.m.clone()
+            torch.cuda.synchronize()
+            opt.close()
+            ctx = B.cser_create(cfg, x2, torch.empty_like(e2), torch.empty_like(m2))
+            B.cser_destroy(ctx)                      # create zero-fills e and m: restore them afterwards
+            e3, m3 = torch.zeros_like(e2), torch.zeros_like(m2)
+            ctx = B.cser_create(cfg, x2, e3, m3)
+            e3.copy_(e2)
+            m3.copy_(m2)
+            B.cser_set_step(ctx, n0)
+            for t in range(n0 + 1, n0 + n1 + 1):
+                B.cser_step(ctx, I.gradient(wl, t, dev))
+            torch.cuda.synchronize()
+            B.cser_destroy(ctx)
+            return x2.cpu(), e3.cpu(), m3.cpu()
+        torch.cuda.synchronize()
+        out = opt.x.cpu(), opt.e.cpu(), opt.m.cpu()
+        opt.close()
+        return out
+
+    straight = run(10, 0)
+    resumed = run(6, 4)
+    for a, b in zip(straight, resumed):
+        assert torch.equal(a, b)
+
+    # a forced reset at an arbitrary t matches the oracle's
+    x = I.initial_model(wl, dev)
+    opt = B.CSER(cfg, x)
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed,
+                     I.initial_model_row(wl, dev).cpu().numpy())
+    for t in range(1, 4):
+        g = I.gradient(wl, t, dev)
+        opt.step(g)
+        o.step(g[:, :wl.d].cpu().numpy())
+    opt.error_reset()
+    o.error_reset()
+    torch.cuda.synchronize()
+    assert assert_states_close("x", opt.x[:, :wl.d].cpu().numpy(), o.x) == 0
+    assert assert_states_close("e", opt.e[:, :wl.d].cpu().numpy(), o.e) == 0
+    opt.close()
+
+
+def test_gpu_run_stays_within_rounding_of_the_float64_oracle():
+    """Independent of the shared fp32 contract: against the oracle in double precision the fp32 states
+    differ by accumulated rounding only (about one rounding of 2^-24 |value| per statement and step)."""
+    dev = torch.device("cuda:0")
+    wl = I.WORKLOADS["tiny"]
+    x = I.initial_model(wl, dev)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, x)
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, float(np.float32(wl.lr)),
+                     float(np.float32(wl.momentum)), wl.seed, I.initial_model_row(wl, dev).cpu().numpy(),
+                     dtype=np.float64)
+    for t in range(1, 101):
+        g = I.gradient(wl, t, dev)
+        opt.step(g)
+        o.step(g[:, :wl.d].cpu().numpy())
+    torch.cuda.synchronize()
+    for name, got, want in (("x", opt.x, o.x), ("e", opt.e, o.e), ("m", opt.m, o.m)):
+        err = np.abs(got[:, :wl.d].cpu().numpy().astype(np.float64) - want)
+        assert err.max() < 100 * 2.0 ** -24 * max(1.0, np.abs(want).max()), (name, err.max())
+    opt.close()
+
+
+def test_profile_counters_and_copy_probe():
+    dev = torch.device("cuda:0")
+    wl = _wl(d=100000, W=8, H=2)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, I.initial_model(wl, dev))
+    B.cser_profile_enable(opt.ctx, True)
+    g = I.gradient(wl, 1, dev)
+    for _ in range(6):
+        opt.step(g)
+    ms0, n0 = B.cser_profile_read(opt.ctx, 0)
+    ms1, n1 = B.cser_profile_read(opt.ctx, 1)
+    assert n0 == 6 and n1 == 3 and ms0 > 0 and ms1 > 0
+    B.cser_profile_clear(opt.ctx)
+    assert B.cser_profile_read(opt.ctx, 0) == (0.0, 0)
+    opt.close()
+    src = torch.arange(1 << 20, device=dev, dtype=torch.float32)
+    dst = torch.zeros_like(src)
+    B.cser_copy_probe(dst, src, src.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)

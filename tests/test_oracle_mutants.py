@@ -26,6 +26,7 @@ MUTANTS = [
     ("model moved the wrong way", "x[i * pb.ld + j] - pprime[i * n + j];\n      e[", "x[i * pb.ld + j] + pprime[i * n + j];\n      e["),
     ("residual accumulated with wrong sign", "e[i * pb.ld + j] = e[i * pb.ld + j] - r[i * n + j]", "e[i * pb.ld + j] = e[i * pb.ld + j] + r[i * n + j]"),
     ("reset forgets to remove the old residual", "(x[i * pb.ld + j] - ehalf[i * n + j]) + eprime[i * n + j]", "x[i * pb.ld + j] + eprime[i * n + j]"),
+    ("reset corrects the model on the unchosen blocks only", "if (chosen[(pb.col0 + j) / pb.block])\n        x[", "if (!chosen[(pb.col0 + j) / pb.block])\n        x["),
     ("reset keeps the old residual", "e[i * pb.ld + j] = r[i * n + j];", "e[i * pb.ld + j] = ehalf[i * n + j];"),
     ("reset reuses the step's blocks", "select_blocks(pb.seed, 1, t, B, blocks_kept(B, R_reset), nullptr, chosen.data());\n  std::vector<real> ehalf", "select_blocks(pb.seed, 0, t, B, blocks_kept(B, R_reset), nullptr, chosen.data());\n  std::vector<real> ehalf"),
     ("compressor keeps the complement", "cv[j] = chosen[b] ? v[j] : real(0)", "cv[j] = chosen[b] ? real(0) : v[j]"),
