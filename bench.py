@@ -54,7 +54,7 @@ def cpu_baseline(wl, seconds_target=15.0):
     import numpy as np
     from oracle import reference as R
     steps = wl.H                                   # one full reset period, so the reset is included
-    nb = max(1, wl.B // 8)
+    nb = max(1, wl.B // 4)
     ncols = min(wl.d, nb * wl.block)
     rng = np.random.default_rng(wl.seed)
     x0 = (rng.standard_normal(ncols) * np.sqrt(wl.x_var)).astype(np.float32)
@@ -165,7 +165,7 @@ def main():
         "worker_elements_per_s": wl.W * wl.d * args.steps / elapsed,
         "whole_path_GBps": (total_step_bytes + total_reset_bytes) / elapsed / 1e9,
         "whole_path_frac_of_peak": (total_step_bytes + total_reset_bytes) / elapsed / 1e9 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "cser_step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "cser_step_rows_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(wl.name),
                      "bytes_per_launch": bytes_per_launch, "ms_per_launch": kernel_ms, "launches": step_launches},
         "reset_kernel": {"launches": reset_launches, "ms_per_launch": reset_ms / max(reset_launches, 1),

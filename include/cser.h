@@ -130,10 +130,15 @@ int cser_profile_read(cser_ctx* ctx, int which, double* total_ms, uint64_t* laun
 int cser_profile_clear(cser_ctx* ctx);
 
 /*
- * Launch shape of the fused-step kernel, for measurement sweeps.  key 0: workgroup cap (0 = one
- * 4-column group per lane; n > 0 = at most n workgroups, lanes loop); key 1: 1 = non-temporal
- * loads/stores, 0 = ordinary; key 2: workers loaded per batch (1, 2, 4 or 8).  Results do not
- * depend on these.
+ * Launch shape of the fused-step kernel, for measurement sweeps; results do not depend on it.
+ *   key 4  kernel variant: 1 (default) = row-split, a workgroup owns one worker's row over a tile of
+ *          columns, tiles vary fastest with the workgroup id; 2 = row-split, workers vary fastest;
+ *          0 = a lane walks all W workers for its 4 columns
+ *   key 3  workgroup size: 64, 128, 256 (default), 512 or 1024
+ *   key 1  1 (default) = non-temporal loads/stores, 0 = ordinary
+ *   key 5  row-split variants: 4-column groups per lane, 1 (default), 2 or 4
+ *   key 0  variant 0: workgroup cap (0 = one group per lane; n > 0 = at most n workgroups, lanes loop)
+ *   key 2  variant 0: workers whose loads are issued together (1, 2, 4 or 8)
  */
 int cser_set_tuning(cser_ctx* ctx, int key, int64_t value);
 

@@ -44,6 +44,9 @@ def _lib():
         if not os.path.exists(LIBRARY):
             raise RuntimeError(f"{LIBRARY} is missing: build it with `python -m paper_2007_13221_amd.build` "
                                "(there is no CPU fallback)")
+        # torch first: the library must bind to the HIP runtime instance torch has loaded, because the
+        # device pointers and streams it is handed belong to that instance
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIBRARY)
         vp, u64, u32, i64 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int64
         L.cser_create.argtypes = [ctypes.POINTER(cser_config), vp, vp, vp, vp, ctypes.POINTER(vp)]

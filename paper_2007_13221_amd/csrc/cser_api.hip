@@ -50,9 +50,13 @@ struct cser_ctx {
   uint32_t k_step, k_reset;
   uint64_t t;
   bool vector_layout;        // ld, block multiples of 4 and x, e, m 16-byte aligned
-  uint8_t* mask_step;        // device, B bytes
+  uint8_t* mask_step;        // device, window * B bytes: C_step's masks for iterations win_t0 .. win_t0 + win_n - 1
+  uint32_t window;           // iterations drawn per selector launch
+  uint64_t win_t0;
+  uint32_t win_n;            // 0: nothing drawn yet
+  hipStream_t win_stream;    // stream the window was drawn on
+  hipEvent_t win_done;       // recorded after the draw; other streams wait on it
   uint8_t* mask_reset;       // device, B bytes
-  uint32_t* idx_step;        // device, max(k_step, 1) entries
   uint32_t* idx_reset;       // device, max(k_reset, 1) entries
   uint8_t* mask_query;       // device scratch of cser_select_blocks, B bytes
   uint32_t* idx_query;       // device scratch of cser_select_blocks, B entries (lazily allocated)
@@ -107,7 +111,7 @@ int drain_timer(Timer& tm) {
 void free_device_arrays(cser_ctx* ctx) {
   if (ctx->mask_step) (void)hipFree(ctx->mask_step);
   if (ctx->mask_reset) (void)hipFree(ctx->mask_reset);
-  if (ctx->idx_step) (void)hipFree(ctx->idx_step);
+  if (ctx->win_done) (void)hipEventDestroy(ctx->win_done);
   if (ctx->idx_reset) (void)hipFree(ctx->idx_reset);
   if (ctx->mask_query) (void)hipFree(ctx->mask_query);
   if (ctx->idx_query) (void)hipFree(ctx->idx_query);
@@ -158,11 +162,17 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
   }
   ctx->profiling = false;
 
-  hipError_t err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_step), ctx->B);
+  // C_step's choice is a pure function of (seed, t): draw up to 32 iterations per selector launch
+  // (fewer when B is so large that the masks would pass 64 MiB), so its latency is paid once per window
+  ctx->window = 32;
+  while (ctx->window > 1 && static_cast<uint64_t>(ctx->window) * ctx->B > (64ull << 20)) ctx->window /= 2;
+  ctx->win_n = 0;
+  ctx->win_t0 = 0;
+  ctx->win_stream = nullptr;
+  hipError_t err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_step), static_cast<uint64_t>(ctx->window) * ctx->B);
+  if (err == hipSuccess) err = hipEventCreateWithFlags(&ctx->win_done, hipEventDisableTiming);
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_reset), ctx->B);
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_query), ctx->B);
-  if (err == hipSuccess)
-    err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_step), sizeof(uint32_t) * (ctx->k_step ? ctx->k_step : 1u));
   if (err == hipSuccess)
     err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_reset), sizeof(uint32_t) * (ctx->k_reset ? ctx->k_reset : 1u));
   if (err != hipSuccess) {
@@ -189,7 +199,7 @@ int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
   if (!ctx) return CSER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (ctx->k_reset == 0) return CSER_OK;
-  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, static_cast<uint32_t>(ctx->B), ctx->k_reset,
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, 1u, static_cast<uint32_t>(ctx->B), ctx->k_reset,
                                  ctx->mask_reset, ctx->idx_reset, s));
   cser::ResetParams p;
   p.x = ctx->x;
@@ -212,14 +222,25 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
   if (!aligned(g, 4)) return CSER_EALIGN;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint64_t t = ctx->t + 1;
-  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 0u, t, static_cast<uint32_t>(ctx->B), ctx->k_step, ctx->mask_step,
-                                 ctx->idx_step, s));
+  if (ctx->win_n == 0 || t < ctx->win_t0 || t - ctx->win_t0 >= ctx->win_n) {
+    // the masks of iterations t .. t + window - 1 (stopping at the largest 64-bit t)
+    uint32_t count = ctx->window;
+    if (UINT64_MAX - t < count - 1) count = static_cast<uint32_t>(UINT64_MAX - t) + 1u;
+    CSER_HIP(cser::launch_selector(ctx->cfg.seed, 0u, t, count, static_cast<uint32_t>(ctx->B), ctx->k_step,
+                                   ctx->mask_step, nullptr, s));
+    CSER_HIP(hipEventRecord(ctx->win_done, s));
+    ctx->win_t0 = t;
+    ctx->win_n = count;
+    ctx->win_stream = s;
+  } else if (s != ctx->win_stream) {
+    CSER_HIP(hipStreamWaitEvent(s, ctx->win_done, 0));   // drawn on another stream: order after it
+  }
   cser::StepParams p;
   p.g = g;
   p.m = ctx->m;
   p.x = ctx->x;
   p.e = ctx->e;
-  p.mask = ctx->mask_step;
+  p.mask = ctx->mask_step + (t - ctx->win_t0) * ctx->B;
   p.ld = ctx->cfg.ld;
   p.d = ctx->cfg.d;
   p.W = ctx->cfg.W;
@@ -254,7 +275,7 @@ int cser_select_blocks(cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host,
     if (err == hipErrorOutOfMemory) return CSER_ENOMEM;
     if (err != hipSuccess) return hip_failed(err, "hipMalloc");
   }
-  CSER_HIP(cser::launch_selector(ctx->cfg.seed, static_cast<uint32_t>(which), t, static_cast<uint32_t>(ctx->B), k,
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, static_cast<uint32_t>(which), t, 1u, static_cast<uint32_t>(ctx->B), k,
                                  ctx->mask_query, ctx->idx_query, nullptr));
   CSER_HIP(hipStreamSynchronize(nullptr));
   if (mask_host) CSER_HIP(hipMemcpy(mask_host, ctx->mask_query, ctx->B, hipMemcpyDeviceToHost));
@@ -328,6 +349,18 @@ int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
     case 2:
       if (value != 1 && value != 2 && value != 4 && value != 8) return CSER_EINVAL;
       ctx->tuning.batch = static_cast<int>(value);
+      return CSER_OK;
+    case 3:
+      if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return CSER_EINVAL;
+      ctx->tuning.threads = static_cast<int>(value);
+      return CSER_OK;
+    case 4:
+      if (value < 0 || value > 2) return CSER_EINVAL;
+      ctx->tuning.variant = static_cast<int>(value);
+      return CSER_OK;
+    case 5:
+      if (value != 1 && value != 2 && value != 4) return CSER_EINVAL;
+      ctx->tuning.cols_per_lane = static_cast<int>(value);
       return CSER_OK;
     default:
       return CSER_EINVAL;

@@ -39,10 +39,14 @@ struct Tuning {
   int64_t wg_cap = 0;   // 0: one 4-column group per lane; > 0: at most this many workgroups
   int nontemporal = 1;
   int batch = 4;        // workers whose loads are issued together
+  int threads = 256;    // workgroup size of the fused-step kernel
+  int variant = 1;      // 0: a lane walks all workers; 1: row-split, tiles fastest; 2: row-split, workers fastest
+  int cols_per_lane = 1;  // row-split variants: 4-column groups per lane
 };
 
-// GRBS block selector (Definition 2): mask[b] = 1 and idx[pi^-1(b)] = b for the k chosen blocks.
-hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t, uint32_t B, uint32_t k,
+// GRBS block selector (Definition 2) for the `count` iterations t0, t0+1, ...: mask[j*B + b] = 1 iff
+// block b is chosen at t0 + j.  idx (may be null, count must be 1): idx[pi^-1(b)] = b for the k chosen.
+hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint32_t count, uint32_t B, uint32_t k,
                            uint8_t* mask, uint32_t* idx, hipStream_t s);
 
 // Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d).  `vectorised` requires ld and

@@ -166,7 +166,7 @@ __device__ __forceinline__ void step_columns(const StepParams& a, uint64_t col, 
 // the number of whole groups.  groups_per_block = block / V (vector path: block % 4 == 0 and
 // col_begin % block == 0, so a group never straddles two blocks).
 template <int V, int U, bool NT, bool HAS_E, bool HAS_M>
-__global__ __launch_bounds__(256) void cser_step_kernel(StepParams a, uint64_t col_begin, uint32_t groups) {
+__global__ __launch_bounds__(1024) void cser_step_kernel(StepParams a, uint64_t col_begin, uint32_t groups) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
   for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; q < groups; q += stride) {
     const uint64_t col = col_begin + q * V;
@@ -174,6 +174,64 @@ __global__ __launch_bounds__(256) void cser_step_kernel(StepParams a, uint64_t c
     if constexpr (V == 4) b = static_cast<uint32_t>(q) / (a.block / 4u);   // vector path starts at column 0
     else b = static_cast<uint32_t>(col / a.block);
     step_columns<V, U, NT, HAS_E, HAS_M>(a, col, a.mask[b] != 0);
+  }
+}
+
+// Row-split variant of the vector path.  A workgroup owns one worker's row over a tile of
+// C * blockDim.x column groups (each lane takes C groups spaced blockDim.x apart, so every access
+// stays coalesced): unchosen blocks need nothing from the other workers.  Chosen blocks need the
+// worker mean; the workgroup of worker 0 walks all rows for those.  WORKER_FASTEST picks which
+// index of the (tile, worker) pair varies fastest with the workgroup id.
+template <int C, bool NT, bool HAS_E, bool HAS_M, bool WORKER_FASTEST>
+__global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint32_t groups, uint32_t tiles) {
+  uint32_t tile, i;
+  if constexpr (WORKER_FASTEST) {
+    tile = blockIdx.x / a.W;
+    i = blockIdx.x - tile * a.W;
+  } else {
+    i = blockIdx.x / tiles;
+    tile = blockIdx.x - i * tiles;
+  }
+  const uint64_t row = static_cast<uint64_t>(i) * a.ld;
+  const uint32_t groups_per_block = a.block / 4u;
+  uint32_t q[C];
+  bool local[C], chosen[C];
+  Pack<4> g[C], m[C], x[C], e[C];
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+    const uint64_t q64 = (static_cast<uint64_t>(tile) * C + c) * blockDim.x + threadIdx.x;
+    const bool live = q64 < groups;
+    q[c] = live ? static_cast<uint32_t>(q64) : 0u;
+    const bool sel = live && a.mask[q[c] / groups_per_block] != 0;
+    local[c] = live && !sel;
+    chosen[c] = sel;
+    if (local[c]) {
+      const uint64_t off = row + static_cast<uint64_t>(q[c]) * 4;
+      g[c] = load_pack<4, NT>(a.g + off);
+      if constexpr (HAS_M) m[c] = load_pack<4, NT>(a.m + off);
+      x[c] = load_pack<4, NT>(a.x + off);
+      if constexpr (HAS_E) e[c] = load_pack<4, NT>(a.e + off);
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < C; ++c) {
+    if (local[c]) {
+      const uint64_t off = row + static_cast<uint64_t>(q[c]) * 4;
+      const Pack<4> p = local_update<4, HAS_M>(a.eta, a.beta, g[c], m[c]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        x[c].v[k] = x[c].v[k] - p.v[k];
+        if constexpr (HAS_E) e[c].v[k] = e[c].v[k] - p.v[k];
+      }
+      if constexpr (HAS_M) store_pack<4, NT>(a.m + off, m[c]);
+      store_pack<4, NT>(a.x + off, x[c]);
+      if constexpr (HAS_E) store_pack<4, NT>(a.e + off, e[c]);
+    }
+  }
+  if (i == 0) {
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+      if (chosen[c]) step_columns<4, 4, NT, HAS_E, HAS_M>(a, static_cast<uint64_t>(q[c]) * 4, true);
   }
 }
 
@@ -268,11 +326,17 @@ __device__ __forceinline__ uint32_t philox_first_word(uint32_t c0, uint32_t c1, 
   return c0;
 }
 
+// blockIdx.y selects the iteration t0 + blockIdx.y (the choice is a pure function of t, so several
+// iterations can be drawn ahead in one launch); its mask goes to mask + blockIdx.y * B.  idx may be
+// null; when given it is only meaningful for a launch with gridDim.y == 1.
 __global__ __launch_bounds__(256) void grbs_select_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
-                                                           uint32_t t_lo, uint32_t t_hi, uint32_t B, uint32_t k,
+                                                           uint64_t t0, uint32_t B, uint32_t k,
                                                            uint32_t half_bits, uint8_t* mask, uint32_t* idx) {
   const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
+  const uint64_t t = t0 + blockIdx.y;
+  const uint32_t t_lo = static_cast<uint32_t>(t), t_hi = static_cast<uint32_t>(t >> 32);
+  mask += static_cast<uint64_t>(blockIdx.y) * B;
   const uint32_t half_mask = (1u << half_bits) - 1u;
   // The network is a bijection of the 2^(2h) values, so the walk from b returns to b after at most
   // 2^(2h) applications and passes a value < B no later than that: the bound below is never the
@@ -295,7 +359,7 @@ __global__ __launch_bounds__(256) void grbs_select_kernel(uint32_t seed_lo, uint
   }
   const bool chosen = v < k;
   mask[b] = chosen ? 1 : 0;
-  if (chosen) idx[v] = b;
+  if (chosen && idx != nullptr) idx[v] = b;
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, uint64_t n) {
@@ -317,23 +381,24 @@ uint32_t half_bits_for(uint32_t B) {
 }
 
 template <int V, int U, bool NT>
-hipError_t launch_step_flags(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, hipStream_t s) {
+hipError_t launch_step_flags(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, uint32_t threads,
+                             hipStream_t s) {
   const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
-  if (has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, true>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
-  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, false>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
-  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, true>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
-  else hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, false>), dim3(grid), dim3(256), 0, s, p, col_begin, groups);
+  if (has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, true>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
+  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, false>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
+  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, true>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
+  else hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, false>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
   return hipGetLastError();
 }
 
 template <int V, bool NT>
-hipError_t launch_step_batch(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, int batch,
-                             hipStream_t s) {
+hipError_t launch_step_batch(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, uint32_t threads,
+                             int batch, hipStream_t s) {
   switch (batch) {
-    case 1: return launch_step_flags<V, 1, NT>(p, col_begin, groups, grid, s);
-    case 2: return launch_step_flags<V, 2, NT>(p, col_begin, groups, grid, s);
-    case 8: return launch_step_flags<V, 8, NT>(p, col_begin, groups, grid, s);
-    default: return launch_step_flags<V, 4, NT>(p, col_begin, groups, grid, s);
+    case 1: return launch_step_flags<V, 1, NT>(p, col_begin, groups, grid, threads, s);
+    case 2: return launch_step_flags<V, 2, NT>(p, col_begin, groups, grid, threads, s);
+    case 8: return launch_step_flags<V, 8, NT>(p, col_begin, groups, grid, threads, s);
+    default: return launch_step_flags<V, 4, NT>(p, col_begin, groups, grid, threads, s);
   }
 }
 
@@ -344,27 +409,63 @@ hipError_t launch_step_range(const StepParams& p, uint64_t col_begin, uint64_t c
   const uint64_t groups64 = (col_end - col_begin) / V;
   if (groups64 == 0) return hipSuccess;
   const uint32_t groups = static_cast<uint32_t>(groups64);
-  uint64_t grid = (groups64 + 255) / 256;
+  const uint32_t threads = static_cast<uint32_t>(tune.threads);
+  uint64_t grid = (groups64 + threads - 1) / threads;
   if (tune.wg_cap > 0 && grid > static_cast<uint64_t>(tune.wg_cap)) grid = static_cast<uint64_t>(tune.wg_cap);
-  if (tune.nontemporal) return launch_step_batch<V, true>(p, col_begin, groups, static_cast<uint32_t>(grid), tune.batch, s);
-  return launch_step_batch<V, false>(p, col_begin, groups, static_cast<uint32_t>(grid), tune.batch, s);
+  if (tune.nontemporal) return launch_step_batch<V, true>(p, col_begin, groups, static_cast<uint32_t>(grid), threads, tune.batch, s);
+  return launch_step_batch<V, false>(p, col_begin, groups, static_cast<uint32_t>(grid), threads, tune.batch, s);
+}
+
+template <int C, bool NT, bool WF>
+hipError_t launch_rows_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t threads, hipStream_t s) {
+  const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
+  const dim3 grid(tiles * p.W), block(threads);
+  if (has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, true, true, WF>), grid, block, 0, s, p, groups, tiles);
+  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, true, false, WF>), grid, block, 0, s, p, groups, tiles);
+  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, false, true, WF>), grid, block, 0, s, p, groups, tiles);
+  else hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, false, false, WF>), grid, block, 0, s, p, groups, tiles);
+  return hipGetLastError();
+}
+
+template <int C>
+hipError_t launch_rows_c(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {
+  const uint32_t threads = static_cast<uint32_t>(tune.threads);
+  const uint64_t per_tile = static_cast<uint64_t>(threads) * C;
+  const uint64_t tiles64 = (groups + per_tile - 1) / per_tile;
+  if (tiles64 * p.W > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+  const uint32_t tiles = static_cast<uint32_t>(tiles64);
+  const bool wf = tune.variant == 2;
+  if (tune.nontemporal) return wf ? launch_rows_flags<C, true, true>(p, groups, tiles, threads, s)
+                                  : launch_rows_flags<C, true, false>(p, groups, tiles, threads, s);
+  return wf ? launch_rows_flags<C, false, true>(p, groups, tiles, threads, s)
+            : launch_rows_flags<C, false, false>(p, groups, tiles, threads, s);
+}
+
+hipError_t launch_rows(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {
+  switch (tune.cols_per_lane) {
+    case 1: return launch_rows_c<1>(p, groups, tune, s);
+    case 4: return launch_rows_c<4>(p, groups, tune, s);
+    default: return launch_rows_c<2>(p, groups, tune, s);
+  }
 }
 
 }  // namespace
 
-hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t, uint32_t B, uint32_t k, uint8_t* mask,
-                           uint32_t* idx, hipStream_t s) {
-  const uint32_t grid = (B + 255u) / 256u;
-  hipLaunchKernelGGL(grbs_select_kernel, dim3(grid), dim3(256), 0, s, static_cast<uint32_t>(seed),
-                     static_cast<uint32_t>(seed >> 32), stream_id, static_cast<uint32_t>(t),
-                     static_cast<uint32_t>(t >> 32), B, k, half_bits_for(B), mask, idx);
+hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint32_t count, uint32_t B, uint32_t k,
+                           uint8_t* mask, uint32_t* idx, hipStream_t s) {
+  if (count == 0) return hipSuccess;
+  const dim3 grid((B + 255u) / 256u, count);
+  hipLaunchKernelGGL(grbs_select_kernel, grid, dim3(256), 0, s, static_cast<uint32_t>(seed),
+                     static_cast<uint32_t>(seed >> 32), stream_id, t0, B, k, half_bits_for(B), mask, idx);
   return hipGetLastError();
 }
 
 hipError_t launch_step(const StepParams& p, bool vectorised, const Tuning& tune, hipStream_t s) {
   if (!vectorised) return launch_step_range<1>(p, 0, p.d, tune, s);
   const uint64_t d4 = p.d & ~3ull;
-  hipError_t err = launch_step_range<4>(p, 0, d4, tune, s);
+  hipError_t err = hipSuccess;
+  if (tune.variant == 0) err = launch_step_range<4>(p, 0, d4, tune, s);
+  else if (d4 > 0) err = launch_rows(p, static_cast<uint32_t>(d4 / 4), tune, s);
   if (err != hipSuccess) return err;
   return launch_step_range<1>(p, d4, p.d, tune, s);   // at most 3 trailing columns
 }
