@@ -78,9 +78,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="large_cnn")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--wg-cap", type=int, default=None)
-    ap.add_argument("--nontemporal", type=int, default=None)
-    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="cser_set_tuning(key, value) before the run (launch-shape experiments)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all W worker states are resident on it and the worker "
@@ -93,15 +92,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
-    wl = I.WORKLOADS[args.workload]
+    named = dict(I.WORKLOADS)
+    named.update({w.name: w for w in I.sweep_workloads()})
+    wl = named[args.workload]
     cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
     opt = B.CSER(cfg, I.initial_model(wl, dev))
-    if args.wg_cap is not None:
-        B.cser_set_tuning(opt.ctx, 0, args.wg_cap)
-    if args.nontemporal is not None:
-        B.cser_set_tuning(opt.ctx, 1, args.nontemporal)
-    if args.batch is not None:
-        B.cser_set_tuning(opt.ctx, 2, args.batch)
+    for item in args.tune:
+        key, value = item.split("=")
+        B.cser_set_tuning(opt.ctx, int(key), int(value))
     grads = [I.gradient(wl, t, dev) for t in (1, 2)]   # generated outside every timed region
     torch.cuda.synchronize()
 

@@ -134,7 +134,7 @@ int cser_profile_clear(cser_ctx* ctx);
  *   key 4  kernel variant: 1 (default) = row-split, a workgroup owns one worker's row over a tile of
  *          columns, tiles vary fastest with the workgroup id; 2 = row-split, workers vary fastest;
  *          0 = a lane walks all W workers for its 4 columns
- *   key 3  workgroup size: 64, 128, 256 (default), 512 or 1024
+ *   key 3  workgroup size: 64 (default), 128, 256, 512 or 1024
  *   key 1  1 (default) = non-temporal loads/stores, 0 = ordinary
  *   key 5  row-split variants: 4-column groups per lane, 1 (default), 2 or 4
  *   key 0  variant 0: workgroup cap (0 = one group per lane; n > 0 = at most n workgroups, lanes loop)

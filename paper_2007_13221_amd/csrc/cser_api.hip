@@ -344,7 +344,8 @@ int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
       ctx->tuning.wg_cap = value;
       return CSER_OK;
     case 1:
-      ctx->tuning.nontemporal = value != 0;
+      if (value < 0 || value > 3) return CSER_EINVAL;
+      ctx->tuning.nontemporal = static_cast<int>(value);
       return CSER_OK;
     case 2:
       if (value != 1 && value != 2 && value != 4 && value != 8) return CSER_EINVAL;
@@ -355,7 +356,7 @@ int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
       ctx->tuning.threads = static_cast<int>(value);
       return CSER_OK;
     case 4:
-      if (value < 0 || value > 2) return CSER_EINVAL;
+      if (value < 0 || value > 3) return CSER_EINVAL;
       ctx->tuning.variant = static_cast<int>(value);
       return CSER_OK;
     case 5:

@@ -37,10 +37,10 @@ struct ResetParams {
 
 struct Tuning {
   int64_t wg_cap = 0;   // 0: one 4-column group per lane; > 0: at most this many workgroups
-  int nontemporal = 1;
+  int nontemporal = 1;  // 0 none, 1 loads and stores, 2 loads only, 3 stores only (variant 0: zero / non-zero)
   int batch = 4;        // workers whose loads are issued together
-  int threads = 256;    // workgroup size of the fused-step kernel
-  int variant = 1;      // 0: a lane walks all workers; 1: row-split, tiles fastest; 2: row-split, workers fastest
+  int threads = 64;     // workgroup size of the fused-step kernel (one wavefront: measured best)
+  int variant = 1;      // 0: a lane walks all workers; row-split: 1 tiles fastest, 2 workers fastest, 3 per-XCD sweeps
   int cols_per_lane = 1;  // row-split variants: 4-column groups per lane
 };
 

@@ -1,15 +1,19 @@
 // HIP kernels of the CSER optimizer update for gfx950 (MI355X), and their launch wrappers.
 //
-//   grbs_select_kernel   the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3)
-//   cser_step_kernel     Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass
-//   cser_reset_kernel    the error-reset branch of Algorithm 3 (PSync(e, C_reset) and the x correction)
+//   grbs_select_kernel      the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3)
+//   cser_step_rows_kernel   Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass
+//   cser_step_kernel        the same, one lane per column group walking all workers (element-wise
+//                           fallback for unaligned layouts; also a measured alternative)
+//   cser_reset_kernel       the error-reset branch of Algorithm 3 (PSync(e, C_reset) and the x correction)
 //
 // The update is a pure stream over HBM (about 6 flops per 28 bytes), so there is no matrix-core
-// work here.  Each lane owns 4 consecutive columns (one 128-bit access per row and array) and
-// walks the worker axis itself: the W-way sum PSync needs is then a private, fixed-order chain of
-// adds in registers -- no LDS, no cross-lane traffic, and the same order as a sequential
-// evaluation.  A wavefront therefore touches 1 KiB contiguous per row and array, and loads of
-// several workers are issued before the first use to keep many requests in flight.
+// work here and nothing to stage in LDS.  States are worker-major rows [W][ld].  On a block that
+// C_step did not choose, every worker's update is independent, so the default kernel gives each
+// workgroup ONE worker's row over a tile of columns: 4 load streams and 3 store streams of
+// 128-bit non-temporal accesses, consecutive workgroups on consecutive tiles.  Only the chosen
+// blocks (1 / R_step of them) need the worker mean; there a lane owns 4 columns and walks the
+// worker axis itself, so the W-way sum is a private, fixed-order chain of adds in registers -- no
+// LDS, no cross-lane traffic, and the same order as a sequential evaluation.
 //
 // Build with -ffp-contract=off: every fused multiply-add below is written out, nothing else fuses.
 
@@ -180,17 +184,30 @@ __global__ __launch_bounds__(1024) void cser_step_kernel(StepParams a, uint64_t 
 // Row-split variant of the vector path.  A workgroup owns one worker's row over a tile of
 // C * blockDim.x column groups (each lane takes C groups spaced blockDim.x apart, so every access
 // stays coalesced): unchosen blocks need nothing from the other workers.  Chosen blocks need the
-// worker mean; the workgroup of worker 0 walks all rows for those.  WORKER_FASTEST picks which
-// index of the (tile, worker) pair varies fastest with the workgroup id.
-template <int C, bool NT, bool HAS_E, bool HAS_M, bool WORKER_FASTEST>
-__global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint32_t groups, uint32_t tiles) {
+// worker mean; the workgroup of worker 0 walks all rows for those.
+// `order` maps the workgroup id to its (worker, tile) pair:
+//   0  tiles fastest: consecutive workgroups sweep one worker's row, then the next worker's
+//   1  workers fastest: consecutive workgroups take the same tile of every worker
+//   2  as 0, but the ids are first regrouped so that each of the 8 XCDs (ids are dealt to them
+//      round-robin) sweeps one contiguous eighth of the (worker, tile) sequence
+// NTMODE: bit 0 = non-temporal loads, bit 1 = non-temporal stores.
+template <int C, int NTMODE, bool HAS_E, bool HAS_M>
+__global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint32_t groups, uint32_t tiles,
+                                                               uint32_t order) {
+  constexpr bool NTL = (NTMODE & 1) != 0, NTS = (NTMODE & 2) != 0;
   uint32_t tile, i;
-  if constexpr (WORKER_FASTEST) {
+  if (order == 1) {
     tile = blockIdx.x / a.W;
     i = blockIdx.x - tile * a.W;
   } else {
-    i = blockIdx.x / tiles;
-    tile = blockIdx.x - i * tiles;
+    uint32_t linear = blockIdx.x;
+    if (order == 2) {
+      const uint32_t per_xcd = gridDim.x / 8u;   // the launcher rounds the grid up to a multiple of 8
+      linear = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+      if (linear >= tiles * a.W) return;
+    }
+    i = linear / tiles;
+    tile = linear - i * tiles;
   }
   const uint64_t row = static_cast<uint64_t>(i) * a.ld;
   const uint32_t groups_per_block = a.block / 4u;
@@ -207,10 +224,10 @@ __global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint
     chosen[c] = sel;
     if (local[c]) {
       const uint64_t off = row + static_cast<uint64_t>(q[c]) * 4;
-      g[c] = load_pack<4, NT>(a.g + off);
-      if constexpr (HAS_M) m[c] = load_pack<4, NT>(a.m + off);
-      x[c] = load_pack<4, NT>(a.x + off);
-      if constexpr (HAS_E) e[c] = load_pack<4, NT>(a.e + off);
+      g[c] = load_pack<4, NTL>(a.g + off);
+      if constexpr (HAS_M) m[c] = load_pack<4, NTL>(a.m + off);
+      x[c] = load_pack<4, NTL>(a.x + off);
+      if constexpr (HAS_E) e[c] = load_pack<4, NTL>(a.e + off);
     }
   }
 #pragma unroll
@@ -223,15 +240,15 @@ __global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint
         x[c].v[k] = x[c].v[k] - p.v[k];
         if constexpr (HAS_E) e[c].v[k] = e[c].v[k] - p.v[k];
       }
-      if constexpr (HAS_M) store_pack<4, NT>(a.m + off, m[c]);
-      store_pack<4, NT>(a.x + off, x[c]);
-      if constexpr (HAS_E) store_pack<4, NT>(a.e + off, e[c]);
+      if constexpr (HAS_M) store_pack<4, NTS>(a.m + off, m[c]);
+      store_pack<4, NTS>(a.x + off, x[c]);
+      if constexpr (HAS_E) store_pack<4, NTS>(a.e + off, e[c]);
     }
   }
   if (i == 0) {
 #pragma unroll
     for (int c = 0; c < C; ++c)
-      if (chosen[c]) step_columns<4, 4, NT, HAS_E, HAS_M>(a, static_cast<uint64_t>(q[c]) * 4, true);
+      if (chosen[c]) step_columns<4, 4, NTL && NTS, HAS_E, HAS_M>(a, static_cast<uint64_t>(q[c]) * 4, true);
   }
 }
 
@@ -416,14 +433,15 @@ hipError_t launch_step_range(const StepParams& p, uint64_t col_begin, uint64_t c
   return launch_step_batch<V, false>(p, col_begin, groups, static_cast<uint32_t>(grid), threads, tune.batch, s);
 }
 
-template <int C, bool NT, bool WF>
-hipError_t launch_rows_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t threads, hipStream_t s) {
+template <int C, int NTMODE>
+hipError_t launch_rows_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t grid_size, uint32_t threads,
+                             uint32_t order, hipStream_t s) {
   const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
-  const dim3 grid(tiles * p.W), block(threads);
-  if (has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, true, true, WF>), grid, block, 0, s, p, groups, tiles);
-  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, true, false, WF>), grid, block, 0, s, p, groups, tiles);
-  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, false, true, WF>), grid, block, 0, s, p, groups, tiles);
-  else hipLaunchKernelGGL((cser_step_rows_kernel<C, NT, false, false, WF>), grid, block, 0, s, p, groups, tiles);
+  const dim3 grid(grid_size), block(threads);
+  if (has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, true>), grid, block, 0, s, p, groups, tiles, order);
+  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, false>), grid, block, 0, s, p, groups, tiles, order);
+  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, true>), grid, block, 0, s, p, groups, tiles, order);
+  else hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, false>), grid, block, 0, s, p, groups, tiles, order);
   return hipGetLastError();
 }
 
@@ -432,13 +450,17 @@ hipError_t launch_rows_c(const StepParams& p, uint32_t groups, const Tuning& tun
   const uint32_t threads = static_cast<uint32_t>(tune.threads);
   const uint64_t per_tile = static_cast<uint64_t>(threads) * C;
   const uint64_t tiles64 = (groups + per_tile - 1) / per_tile;
-  if (tiles64 * p.W > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-  const uint32_t tiles = static_cast<uint32_t>(tiles64);
-  const bool wf = tune.variant == 2;
-  if (tune.nontemporal) return wf ? launch_rows_flags<C, true, true>(p, groups, tiles, threads, s)
-                                  : launch_rows_flags<C, true, false>(p, groups, tiles, threads, s);
-  return wf ? launch_rows_flags<C, false, true>(p, groups, tiles, threads, s)
-            : launch_rows_flags<C, false, false>(p, groups, tiles, threads, s);
+  const uint32_t order = tune.variant == 2 ? 1u : (tune.variant == 3 ? 2u : 0u);
+  uint64_t grid64 = tiles64 * p.W;
+  if (order == 2) grid64 = (grid64 + 7) / 8 * 8;
+  if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+  const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
+  switch (tune.nontemporal) {
+    case 0: return launch_rows_flags<C, 0>(p, groups, tiles, grid, threads, order, s);
+    case 2: return launch_rows_flags<C, 1>(p, groups, tiles, grid, threads, order, s);
+    case 3: return launch_rows_flags<C, 2>(p, groups, tiles, grid, threads, order, s);
+    default: return launch_rows_flags<C, 3>(p, groups, tiles, grid, threads, order, s);
+  }
 }
 
 hipError_t launch_rows(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {

@@ -174,7 +174,10 @@ def test_no_momentum_buffer_is_algorithm_2():
     assert run_pair(wl, 12, with_momentum=False, with_error=False) == 0
 
 
-@pytest.mark.parametrize("tuning", [{0: 1}, {0: 7}, {1: 0}, {2: 1}, {2: 2}, {2: 8}, {0: 3, 1: 0, 2: 8}])
+@pytest.mark.parametrize("tuning", [{4: 0}, {4: 0, 0: 1}, {4: 0, 0: 7}, {4: 0, 1: 0}, {4: 0, 2: 1}, {4: 0, 2: 2},
+                                    {4: 0, 2: 8}, {4: 0, 0: 3, 1: 0, 2: 8}, {4: 0, 3: 64}, {4: 0, 3: 1024},
+                                    {4: 1, 5: 2}, {4: 1, 5: 4, 3: 512}, {4: 2}, {4: 2, 5: 2, 3: 128}, {4: 3},
+                                    {4: 3, 3: 64, 5: 4}, {1: 0}, {1: 2}, {1: 3}, {3: 64}, {3: 1024}])
 def test_results_do_not_depend_on_launch_shape(tuning):
     wl = _wl(d=30000, W=8, steps=8)
     assert run_pair(wl, 8, tuning=tuning) == 0
@@ -236,6 +239,59 @@ def test_forced_reset_and_resume_from_checkpoint():
     torch.cuda.synchronize()
     assert assert_states_close("x", opt.x[:, :wl.d].cpu().numpy(), o.x) == 0
     assert assert_states_close("e", opt.e[:, :wl.d].cpu().numpy(), o.e) == 0
+    opt.close()
+
+
+def test_step_counter_jumps_across_the_mask_window():
+    """C_step's masks are drawn 32 iterations per selector launch; moving t backwards, forwards and
+    across window edges must still use the mask of the iteration actually being run."""
+    dev = torch.device("cuda:0")
+    wl = _wl(d=9000, W=4, H=5)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, I.initial_model(wl, dev))
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed,
+                     I.initial_model_row(wl, dev).cpu().numpy())
+    schedule = [(0, 35), (3, 4), (31, 4), (2**32 - 2, 4), (2**64 - 40, 36), (64, 2), (63, 3)]
+    n = 0
+    for start, count in schedule:
+        B.cser_set_step(opt.ctx, start)
+        o.t = start
+        for _ in range(count):
+            n += 1
+            g = I.gradient(wl, n, dev)
+            opt.step(g)
+            o.step(g[:, :wl.d].cpu().numpy())
+        assert B.cser_get_step(opt.ctx) == o.t == start + count
+    torch.cuda.synchronize()
+    for name in ("x", "e", "m"):
+        assert assert_states_close(name, getattr(opt, name)[:, :wl.d].cpu().numpy(), getattr(o, name)) == 0
+    opt.close()
+
+
+def test_steps_issued_on_alternating_streams():
+    """The caller orders its own work between streams; the library orders the mask window it drew on
+    one stream before the step kernels it launches on another."""
+    dev = torch.device("cuda:0")
+    wl = _wl(d=200000, W=8, H=3)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, I.initial_model(wl, dev))
+    torch.cuda.synchronize()
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed,
+                     I.initial_model_row(wl, dev).cpu().numpy())
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    grads = [I.gradient(wl, t, dev) for t in range(1, 11)]
+    torch.cuda.synchronize()
+    prev = None
+    for t, g in enumerate(grads, start=1):
+        s = streams[t & 1]
+        if prev is not None:
+            s.wait_stream(prev)
+        opt.step(g, stream=s)
+        prev = s
+        o.step(g[:, :wl.d].cpu().numpy())
+    torch.cuda.synchronize()
+    for name in ("x", "e", "m"):
+        assert assert_states_close(name, getattr(opt, name)[:, :wl.d].cpu().numpy(), getattr(o, name)) == 0
     opt.close()
 
 
