@@ -50,7 +50,7 @@ typedef struct cser_ctx cser_ctx; /* opaque, host-side */
 
 typedef struct cser_config {
   uint64_t d;        /* parameters per worker, >= 1                                                       */
-  uint64_t ld;       /* row stride of x, e, m, g in elements, >= d                                        */
+  uint64_t ld;       /* row stride of x, e, m, g in elements, >= d; a multiple of 1024 (4 KiB rows) is fastest */
   uint32_t W;        /* number of workers n, >= 1 (Section 3)                                             */
   uint32_t block;    /* elements per GRBS block, >= 1; B = ceil(d / block) (Definition 2)                 */
   uint32_t R_step;   /* ratio of the per-iteration compressor (paper: R_C2): keeps ceil(B / R_step)
@@ -80,7 +80,8 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
 /*
  * One iteration: t <- t + 1; block selection for (seed, stream 0, t); the fused local step,
  * partial synchronisation and residual bookkeeping (the four statements of Algorithm 3 before
- * its "if"); then, when H > 0 and t mod H = 0, the error reset of cser_error_reset().
+ * its "if"); then, when H > 0 and t mod H = 0, the error reset (same result as cser_error_reset();
+ * by default it is carried out inside the same kernel pass).
  *   g  device [W][ld] fp32, read-only: this iteration's stochastic gradients, one row per worker.
  * Arithmetic: beta*m+g and beta*m_new+g are single fused multiply-adds, the worker mean is the
  * left-to-right sum over i = 0..W-1 divided by W, everything in fp32.
@@ -137,6 +138,9 @@ int cser_profile_clear(cser_ctx* ctx);
  *   key 3  workgroup size: 64 (default), 128, 256, 512 or 1024
  *   key 1  1 (default) = non-temporal loads/stores, 0 = ordinary
  *   key 5  row-split variants: 4-column groups per lane, 1 (default), 2 or 4
+ *   key 6  1 (default) = on iterations with t mod H = 0 the error reset runs inside the fused-step kernel
+ *          (x and e of the reset blocks make one trip instead of two); 0 = separate reset kernel
+ *   key 7  bytes of (unused) dynamic LDS per workgroup, 0 .. 65536 (default 10240): caps workgroups per CU
  *   key 0  variant 0: workgroup cap (0 = one group per lane; n > 0 = at most n workgroups, lanes loop)
  *   key 2  variant 0: workers whose loads are issued together (1, 2, 4 or 8)
  */

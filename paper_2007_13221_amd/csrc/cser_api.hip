@@ -56,7 +56,10 @@ struct cser_ctx {
   uint32_t win_n;            // 0: nothing drawn yet
   hipStream_t win_stream;    // stream the window was drawn on
   hipEvent_t win_done;       // recorded after the draw; other streams wait on it
-  uint8_t* mask_reset;       // device, B bytes
+  uint8_t* mask_reset;       // device, B bytes: C_reset's mask of an explicit cser_error_reset
+  uint8_t* mask_reset_win;   // device, window * B bytes: C_reset's masks of the reset iterations inside the window
+  uint64_t win_reset_t0;     // first reset iteration (multiple of H) in the window
+  uint32_t win_reset_n;      // number of reset iterations in the window
   uint32_t* idx_reset;       // device, max(k_reset, 1) entries
   uint8_t* mask_query;       // device scratch of cser_select_blocks, B bytes
   uint32_t* idx_query;       // device scratch of cser_select_blocks, B entries (lazily allocated)
@@ -111,6 +114,7 @@ int drain_timer(Timer& tm) {
 void free_device_arrays(cser_ctx* ctx) {
   if (ctx->mask_step) (void)hipFree(ctx->mask_step);
   if (ctx->mask_reset) (void)hipFree(ctx->mask_reset);
+  if (ctx->mask_reset_win) (void)hipFree(ctx->mask_reset_win);
   if (ctx->win_done) (void)hipEventDestroy(ctx->win_done);
   if (ctx->idx_reset) (void)hipFree(ctx->idx_reset);
   if (ctx->mask_query) (void)hipFree(ctx->mask_query);
@@ -171,6 +175,10 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
   ctx->win_stream = nullptr;
   hipError_t err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_step), static_cast<uint64_t>(ctx->window) * ctx->B);
   if (err == hipSuccess) err = hipEventCreateWithFlags(&ctx->win_done, hipEventDisableTiming);
+  if (err == hipSuccess && cfg->H > 0)
+    err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_reset_win), static_cast<uint64_t>(ctx->window) * ctx->B);
+  ctx->win_reset_t0 = 0;
+  ctx->win_reset_n = 0;
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_reset), ctx->B);
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_query), ctx->B);
   if (err == hipSuccess)
@@ -199,7 +207,7 @@ int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
   if (!ctx) return CSER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (ctx->k_reset == 0) return CSER_OK;
-  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, 1u, static_cast<uint32_t>(ctx->B), ctx->k_reset,
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, 0u, 1u, static_cast<uint32_t>(ctx->B), ctx->k_reset,
                                  ctx->mask_reset, ctx->idx_reset, s));
   cser::ResetParams p;
   p.x = ctx->x;
@@ -226,8 +234,22 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
     // the masks of iterations t .. t + window - 1 (stopping at the largest 64-bit t)
     uint32_t count = ctx->window;
     if (UINT64_MAX - t < count - 1) count = static_cast<uint32_t>(UINT64_MAX - t) + 1u;
-    CSER_HIP(cser::launch_selector(ctx->cfg.seed, 0u, t, count, static_cast<uint32_t>(ctx->B), ctx->k_step,
+    CSER_HIP(cser::launch_selector(ctx->cfg.seed, 0u, t, 1u, count, static_cast<uint32_t>(ctx->B), ctx->k_step,
                                    ctx->mask_step, nullptr, s));
+    // and C_reset's masks of the reset iterations (multiples of H) among them, for the fused reset
+    ctx->win_reset_n = 0;
+    const uint64_t H = ctx->cfg.H;
+    if (H > 0 && ctx->tuning.fuse_reset) {
+      const uint64_t last = t + (count - 1);
+      const uint64_t rem = t % H;
+      const uint64_t gap = rem == 0 ? 0 : H - rem;
+      if (gap <= last - t) {
+        ctx->win_reset_t0 = t + gap;
+        ctx->win_reset_n = static_cast<uint32_t>((last - ctx->win_reset_t0) / H) + 1u;
+        CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->win_reset_t0, H, ctx->win_reset_n,
+                                       static_cast<uint32_t>(ctx->B), ctx->k_reset, ctx->mask_reset_win, nullptr, s));
+      }
+    }
     CSER_HIP(hipEventRecord(ctx->win_done, s));
     ctx->win_t0 = t;
     ctx->win_n = count;
@@ -241,6 +263,10 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
   p.x = ctx->x;
   p.e = ctx->e;
   p.mask = ctx->mask_step + (t - ctx->win_t0) * ctx->B;
+  const bool reset_now = ctx->cfg.H > 0 && t % ctx->cfg.H == 0;
+  const bool fused = reset_now && ctx->tuning.fuse_reset && ctx->win_reset_n > 0 && t >= ctx->win_reset_t0 &&
+                     (t - ctx->win_reset_t0) / ctx->cfg.H < ctx->win_reset_n;
+  p.reset_mask = fused ? ctx->mask_reset_win + ((t - ctx->win_reset_t0) / ctx->cfg.H) * ctx->B : nullptr;
   p.ld = ctx->cfg.ld;
   p.d = ctx->cfg.d;
   p.W = ctx->cfg.W;
@@ -254,7 +280,7 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
   rc = record_end(ctx, 0, s, timed);
   if (rc != CSER_OK) return rc;
   ctx->t = t;
-  if (ctx->cfg.H > 0 && t % ctx->cfg.H == 0) return cser_error_reset(ctx, hip_stream);
+  if (reset_now && !fused) return cser_error_reset(ctx, hip_stream);
   return CSER_OK;
 }
 
@@ -275,7 +301,7 @@ int cser_select_blocks(cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host,
     if (err == hipErrorOutOfMemory) return CSER_ENOMEM;
     if (err != hipSuccess) return hip_failed(err, "hipMalloc");
   }
-  CSER_HIP(cser::launch_selector(ctx->cfg.seed, static_cast<uint32_t>(which), t, 1u, static_cast<uint32_t>(ctx->B), k,
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, static_cast<uint32_t>(which), t, 0u, 1u, static_cast<uint32_t>(ctx->B), k,
                                  ctx->mask_query, ctx->idx_query, nullptr));
   CSER_HIP(hipStreamSynchronize(nullptr));
   if (mask_host) CSER_HIP(hipMemcpy(mask_host, ctx->mask_query, ctx->B, hipMemcpyDeviceToHost));
@@ -362,6 +388,14 @@ int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
     case 5:
       if (value != 1 && value != 2 && value != 4) return CSER_EINVAL;
       ctx->tuning.cols_per_lane = static_cast<int>(value);
+      return CSER_OK;
+    case 7:
+      if (value < 0 || value > 65536) return CSER_EINVAL;
+      ctx->tuning.lds_bytes = static_cast<int>(value);
+      return CSER_OK;
+    case 6:
+      ctx->tuning.fuse_reset = value != 0;
+      ctx->win_n = 0;   // the window is redrawn with (or without) C_reset's masks
       return CSER_OK;
     default:
       return CSER_EINVAL;

@@ -16,6 +16,7 @@ struct StepParams {
   float* x;
   float* e;
   const uint8_t* mask;  // B bytes, 1 = block chosen by C_step for this t
+  const uint8_t* reset_mask;  // null, or B bytes: blocks C_reset chose at this t; the reset is then done in the same pass
   uint64_t ld;
   uint64_t d;
   uint32_t W;
@@ -41,13 +42,16 @@ struct Tuning {
   int batch = 4;        // workers whose loads are issued together
   int threads = 64;     // workgroup size of the fused-step kernel (one wavefront: measured best)
   int variant = 1;      // 0: a lane walks all workers; row-split: 1 tiles fastest, 2 workers fastest, 3 per-XCD sweeps
+  int lds_bytes = 10240;  // dynamic LDS requested per workgroup and never touched: caps a CU at 16 one-wavefront
+                          // workgroups (4 per SIMD); measured 4-5 % faster than uncapped (up to 32), plateau 14..20
+  int fuse_reset = 1;   // on reset iterations do the error reset inside the fused-step kernel
   int cols_per_lane = 1;  // row-split variants: 4-column groups per lane
 };
 
-// GRBS block selector (Definition 2) for the `count` iterations t0, t0+1, ...: mask[j*B + b] = 1 iff
-// block b is chosen at t0 + j.  idx (may be null, count must be 1): idx[pi^-1(b)] = b for the k chosen.
-hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint32_t count, uint32_t B, uint32_t k,
-                           uint8_t* mask, uint32_t* idx, hipStream_t s);
+// GRBS block selector (Definition 2) for the `count` iterations t0, t0 + t_stride, ...: mask[j*B + b] = 1 iff
+// block b is chosen at the j-th of them.  idx (may be null, count must be 1): idx[pi^-1(b)] = b for the k chosen.
+hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint64_t t_stride, uint32_t count, uint32_t B,
+                           uint32_t k, uint8_t* mask, uint32_t* idx, hipStream_t s);
 
 // Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d).  `vectorised` requires ld and
 // block multiples of 4 and 16-byte aligned rows.

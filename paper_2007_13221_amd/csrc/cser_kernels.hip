@@ -1,6 +1,7 @@
 // HIP kernels of the CSER optimizer update for gfx950 (MI355X), and their launch wrappers.
 //
-//   grbs_select_kernel      the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3)
+//   grbs_select_kernel      the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3),
+//   grbs_scatter_kernel     from the blocks' side (inverse permutation) or from the draws' side (forward)
 //   cser_step_rows_kernel   Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass
 //   cser_step_kernel        the same, one lane per column group walking all workers (element-wise
 //                           fallback for unaligned layouts; also a measured alternative)
@@ -166,6 +167,83 @@ __device__ __forceinline__ void step_columns(const StepParams& a, uint64_t col, 
   }
 }
 
+// Reset iterations (t mod H = 0) with the reset fused into the step: the V columns at `col` belong
+// to a block C_reset chose, so after the step's own update the error reset follows at once,
+//   ebar = (e'_0 + ... + e'_{W-1}) / W ;  x_i <- (x'_i - e'_i) + ebar ;  e_i <- +0
+// (implementation II: x_i <- (x'_0 + ... + x'_{W-1}) / W), where x', e' are the values after the
+// step.  Every operation and its order are those of running the step kernel and then the reset
+// kernel; x and e just travel through registers instead of memory.  A worker's update p_i is
+// recomputed from g_i and the old m_i in each pass (m is stored only in the last), so no pass reads
+// what an earlier pass wrote.  Plain (temporal) accesses: the re-reads are meant to hit in L2.
+template <int V, bool HAS_E, bool HAS_M>
+__device__ __forceinline__ void step_and_reset_columns(const StepParams& a, uint64_t col, bool step_chosen) {
+  const float n = static_cast<float>(a.W);
+  Pack<V> pbar, sum, mean, zero;
+#pragma unroll
+  for (int c = 0; c < V; ++c) {
+    pbar.v[c] = 0.0f;
+    sum.v[c] = 0.0f;
+    zero.v[c] = 0.0f;
+  }
+  if (step_chosen) {   // pbar = mean_i p_i
+    Pack<V> psum = zero;
+    for (uint32_t i = 0; i < a.W; ++i) {
+      const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
+      const Pack<V> g = load_pack<V, false>(a.g + off);
+      Pack<V> m = zero;
+      if constexpr (HAS_M) m = load_pack<V, false>(a.m + off);
+      const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g, m);
+#pragma unroll
+      for (int c = 0; c < V; ++c) psum.v[c] = psum.v[c] + p.v[c];
+    }
+#pragma unroll
+    for (int c = 0; c < V; ++c) pbar.v[c] = psum.v[c] / n;
+  }
+  // worker sum of what the reset averages: e after the step (implementation I) or x after the step (II)
+  for (uint32_t i = 0; i < a.W; ++i) {
+    const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
+    Pack<V> v = load_pack<V, false>((HAS_E ? a.e : a.x) + off);
+    if (!step_chosen) {
+      const Pack<V> g = load_pack<V, false>(a.g + off);
+      Pack<V> m = zero;
+      if constexpr (HAS_M) m = load_pack<V, false>(a.m + off);
+      const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g, m);
+#pragma unroll
+      for (int c = 0; c < V; ++c) v.v[c] = v.v[c] - p.v[c];        // e - r  or  x - p'
+    } else if constexpr (!HAS_E) {
+#pragma unroll
+      for (int c = 0; c < V; ++c) v.v[c] = v.v[c] - pbar.v[c];     // x - pbar (e is untouched on chosen blocks)
+    }
+#pragma unroll
+    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + v.v[c];
+  }
+#pragma unroll
+  for (int c = 0; c < V; ++c) mean.v[c] = sum.v[c] / n;
+  // apply
+  for (uint32_t i = 0; i < a.W; ++i) {
+    const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
+    const Pack<V> g = load_pack<V, false>(a.g + off);
+    Pack<V> m = zero;
+    if constexpr (HAS_M) m = load_pack<V, false>(a.m + off);
+    const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g, m);
+    if constexpr (HAS_M) store_pack<V, false>(a.m + off, m);
+    if constexpr (HAS_E) {
+      Pack<V> x = load_pack<V, false>(a.x + off);
+      Pack<V> e = load_pack<V, false>(a.e + off);
+#pragma unroll
+      for (int c = 0; c < V; ++c) {
+        x.v[c] = x.v[c] - (step_chosen ? pbar.v[c] : p.v[c]);
+        if (!step_chosen) e.v[c] = e.v[c] - p.v[c];
+        x.v[c] = (x.v[c] - e.v[c]) + mean.v[c];
+      }
+      store_pack<V, false>(a.x + off, x);
+      store_pack<V, false>(a.e + off, zero);
+    } else {
+      store_pack<V, false>(a.x + off, mean);
+    }
+  }
+}
+
 // Columns [col_begin, col_end) in groups of V; group q covers col_begin + q*V ...  `groups` is
 // the number of whole groups.  groups_per_block = block / V (vector path: block % 4 == 0 and
 // col_begin % block == 0, so a group never straddles two blocks).
@@ -177,14 +255,17 @@ __global__ __launch_bounds__(1024) void cser_step_kernel(StepParams a, uint64_t 
     uint32_t b;
     if constexpr (V == 4) b = static_cast<uint32_t>(q) / (a.block / 4u);   // vector path starts at column 0
     else b = static_cast<uint32_t>(col / a.block);
-    step_columns<V, U, NT, HAS_E, HAS_M>(a, col, a.mask[b] != 0);
+    const bool step_chosen = a.mask[b] != 0;
+    if (a.reset_mask != nullptr && a.reset_mask[b] != 0) step_and_reset_columns<V, HAS_E, HAS_M>(a, col, step_chosen);
+    else step_columns<V, U, NT, HAS_E, HAS_M>(a, col, step_chosen);
   }
 }
 
 // Row-split variant of the vector path.  A workgroup owns one worker's row over a tile of
 // C * blockDim.x column groups (each lane takes C groups spaced blockDim.x apart, so every access
 // stays coalesced): unchosen blocks need nothing from the other workers.  Chosen blocks need the
-// worker mean; the workgroup of worker 0 walks all rows for those.
+// worker mean (and so do the blocks C_reset chose, on a reset iteration with the reset fused in);
+// the workgroup of worker 0 walks all rows for those.
 // `order` maps the workgroup id to its (worker, tile) pair:
 //   0  tiles fastest: consecutive workgroups sweep one worker's row, then the next worker's
 //   1  workers fastest: consecutive workgroups take the same tile of every worker
@@ -212,16 +293,17 @@ __global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint
   const uint64_t row = static_cast<uint64_t>(i) * a.ld;
   const uint32_t groups_per_block = a.block / 4u;
   uint32_t q[C];
-  bool local[C], chosen[C];
+  bool local[C], chosen[C], reset_chosen[C];
   Pack<4> g[C], m[C], x[C], e[C];
 #pragma unroll
   for (int c = 0; c < C; ++c) {
     const uint64_t q64 = (static_cast<uint64_t>(tile) * C + c) * blockDim.x + threadIdx.x;
     const bool live = q64 < groups;
     q[c] = live ? static_cast<uint32_t>(q64) : 0u;
-    const bool sel = live && a.mask[q[c] / groups_per_block] != 0;
-    local[c] = live && !sel;
-    chosen[c] = sel;
+    const uint32_t b = q[c] / groups_per_block;
+    chosen[c] = live && a.mask[b] != 0;
+    reset_chosen[c] = live && a.reset_mask != nullptr && a.reset_mask[b] != 0;
+    local[c] = live && !chosen[c] && !reset_chosen[c];
     if (local[c]) {
       const uint64_t off = row + static_cast<uint64_t>(q[c]) * 4;
       g[c] = load_pack<4, NTL>(a.g + off);
@@ -247,8 +329,11 @@ __global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint
   }
   if (i == 0) {
 #pragma unroll
-    for (int c = 0; c < C; ++c)
-      if (chosen[c]) step_columns<4, 4, NTL && NTS, HAS_E, HAS_M>(a, static_cast<uint64_t>(q[c]) * 4, true);
+    for (int c = 0; c < C; ++c) {
+      const uint64_t col = static_cast<uint64_t>(q[c]) * 4;
+      if (reset_chosen[c]) step_and_reset_columns<4, HAS_E, HAS_M>(a, col, chosen[c]);
+      else if (chosen[c]) step_columns<4, 4, NTL && NTS, HAS_E, HAS_M>(a, col, true);
+    }
   }
 }
 
@@ -343,15 +428,15 @@ __device__ __forceinline__ uint32_t philox_first_word(uint32_t c0, uint32_t c1, 
   return c0;
 }
 
-// blockIdx.y selects the iteration t0 + blockIdx.y (the choice is a pure function of t, so several
+// blockIdx.y selects the iteration t0 + blockIdx.y * t_stride (the choice is a pure function of t, so several
 // iterations can be drawn ahead in one launch); its mask goes to mask + blockIdx.y * B.  idx may be
 // null; when given it is only meaningful for a launch with gridDim.y == 1.
 __global__ __launch_bounds__(256) void grbs_select_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
-                                                           uint64_t t0, uint32_t B, uint32_t k,
+                                                           uint64_t t0, uint64_t t_stride, uint32_t B, uint32_t k,
                                                            uint32_t half_bits, uint8_t* mask, uint32_t* idx) {
   const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
-  const uint64_t t = t0 + blockIdx.y;
+  const uint64_t t = t0 + blockIdx.y * t_stride;
   const uint32_t t_lo = static_cast<uint32_t>(t), t_hi = static_cast<uint32_t>(t >> 32);
   mask += static_cast<uint64_t>(blockIdx.y) * B;
   const uint32_t half_mask = (1u << half_bits) - 1u;
@@ -377,6 +462,47 @@ __global__ __launch_bounds__(256) void grbs_select_kernel(uint32_t seed_lo, uint
   const bool chosen = v < k;
   mask[b] = chosen ? 1 : 0;
   if (chosen && idx != nullptr) idx[v] = b;
+}
+
+// The same choice from the other side: thread j < k evaluates pi(j) with the forward network and
+// marks that block in a mask that was zeroed beforehand.  k evaluations instead of B, so this is the
+// cheaper form whenever the compressor keeps less than half of the blocks; both forms give the same
+// mask because pi is a bijection.
+__global__ __launch_bounds__(256) void grbs_scatter_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
+                                                            uint64_t t0, uint64_t t_stride, uint32_t B, uint32_t k,
+                                                            uint32_t half_bits, uint8_t* mask, uint32_t* idx) {
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= k) return;
+  const uint64_t t = t0 + blockIdx.y * t_stride;
+  const uint32_t t_lo = static_cast<uint32_t>(t), t_hi = static_cast<uint32_t>(t >> 32);
+  mask += static_cast<uint64_t>(blockIdx.y) * B;
+  const uint32_t half_mask = (1u << half_bits) - 1u;
+  const uint64_t domain = 1ull << (2 * half_bits);   // bound of the cycle walk, as in grbs_select_kernel
+  uint32_t v = j;
+  for (uint64_t walk = 0; walk < domain; ++walk) {
+    uint32_t left = (v >> half_bits) & half_mask;
+    uint32_t right = v & half_mask;
+    for (uint32_t round = 0; round < 8; ++round) {   // (L, R) -> (R, L ^ F(round, R))
+      const uint32_t f = philox_first_word(right, stream_id * 65536u + round, t_lo, t_hi, seed_lo, seed_hi) & half_mask;
+      const uint32_t next_right = left ^ f;
+      left = right;
+      right = next_right;
+    }
+    v = (left << half_bits) | right;
+    if (v < B) break;
+  }
+  if (v < B) {   // always true (see the bound above); keeps a write in range whatever happens
+    mask[v] = 1;
+    if (idx != nullptr) idx[j] = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_bytes_zero_kernel(uint8_t* p, uint64_t n) {
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
+  const uint64_t n4 = n / 4;   // p comes from hipMalloc: 4-byte aligned
+  uint32_t* p4 = reinterpret_cast<uint32_t*>(p);
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) p4[i] = 0u;
+  if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) p[n4 * 4 + threadIdx.x] = 0;
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, uint64_t n) {
@@ -435,13 +561,13 @@ hipError_t launch_step_range(const StepParams& p, uint64_t col_begin, uint64_t c
 
 template <int C, int NTMODE>
 hipError_t launch_rows_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t grid_size, uint32_t threads,
-                             uint32_t order, hipStream_t s) {
+                             uint32_t order, uint32_t lds, hipStream_t s) {
   const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
   const dim3 grid(grid_size), block(threads);
-  if (has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, true>), grid, block, 0, s, p, groups, tiles, order);
-  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, false>), grid, block, 0, s, p, groups, tiles, order);
-  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, true>), grid, block, 0, s, p, groups, tiles, order);
-  else hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, false>), grid, block, 0, s, p, groups, tiles, order);
+  if (has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, true>), grid, block, lds, s, p, groups, tiles, order);
+  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, false>), grid, block, lds, s, p, groups, tiles, order);
+  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, true>), grid, block, lds, s, p, groups, tiles, order);
+  else hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, false>), grid, block, lds, s, p, groups, tiles, order);
   return hipGetLastError();
 }
 
@@ -455,11 +581,12 @@ hipError_t launch_rows_c(const StepParams& p, uint32_t groups, const Tuning& tun
   if (order == 2) grid64 = (grid64 + 7) / 8 * 8;
   if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
+  const uint32_t lds = static_cast<uint32_t>(tune.lds_bytes);   // unused by the kernel: only caps workgroups per CU
   switch (tune.nontemporal) {
-    case 0: return launch_rows_flags<C, 0>(p, groups, tiles, grid, threads, order, s);
-    case 2: return launch_rows_flags<C, 1>(p, groups, tiles, grid, threads, order, s);
-    case 3: return launch_rows_flags<C, 2>(p, groups, tiles, grid, threads, order, s);
-    default: return launch_rows_flags<C, 3>(p, groups, tiles, grid, threads, order, s);
+    case 0: return launch_rows_flags<C, 0>(p, groups, tiles, grid, threads, order, lds, s);
+    case 2: return launch_rows_flags<C, 1>(p, groups, tiles, grid, threads, order, lds, s);
+    case 3: return launch_rows_flags<C, 2>(p, groups, tiles, grid, threads, order, lds, s);
+    default: return launch_rows_flags<C, 3>(p, groups, tiles, grid, threads, order, lds, s);
   }
 }
 
@@ -473,12 +600,27 @@ hipError_t launch_rows(const StepParams& p, uint32_t groups, const Tuning& tune,
 
 }  // namespace
 
-hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint32_t count, uint32_t B, uint32_t k,
-                           uint8_t* mask, uint32_t* idx, hipStream_t s) {
+hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint64_t t_stride, uint32_t count, uint32_t B,
+                           uint32_t k, uint8_t* mask, uint32_t* idx, hipStream_t s) {
   if (count == 0) return hipSuccess;
+  const uint32_t seed_lo = static_cast<uint32_t>(seed), seed_hi = static_cast<uint32_t>(seed >> 32);
+  if (static_cast<uint64_t>(k) * 2 < B) {
+    // few blocks kept: zero the masks, then one forward evaluation per kept block
+    const uint64_t bytes = static_cast<uint64_t>(count) * B;
+    uint64_t fill_grid = (bytes / 4 + 255) / 256;
+    if (fill_grid > 4096) fill_grid = 4096;
+    if (fill_grid == 0) fill_grid = 1;
+    hipLaunchKernelGGL(fill_bytes_zero_kernel, dim3(static_cast<uint32_t>(fill_grid)), dim3(256), 0, s, mask, bytes);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || k == 0) return err;
+    const dim3 grid((k + 255u) / 256u, count);
+    hipLaunchKernelGGL(grbs_scatter_kernel, grid, dim3(256), 0, s, seed_lo, seed_hi, stream_id, t0, t_stride, B, k,
+                       half_bits_for(B), mask, idx);
+    return hipGetLastError();
+  }
   const dim3 grid((B + 255u) / 256u, count);
-  hipLaunchKernelGGL(grbs_select_kernel, grid, dim3(256), 0, s, static_cast<uint32_t>(seed),
-                     static_cast<uint32_t>(seed >> 32), stream_id, t0, B, k, half_bits_for(B), mask, idx);
+  hipLaunchKernelGGL(grbs_select_kernel, grid, dim3(256), 0, s, seed_lo, seed_hi, stream_id, t0, t_stride, B, k,
+                     half_bits_for(B), mask, idx);
   return hipGetLastError();
 }
 
@@ -525,6 +667,8 @@ hipError_t launch_fill_zero(float* ptr, uint64_t n, hipStream_t s) {
 hipError_t launch_copy(void* dst, const void* src, uint64_t n_bytes, hipStream_t s) {
   const uint64_t n16 = n_bytes / 16;
   if (n16 == 0) return hipSuccess;
+  // 256-lane workgroups, no occupancy cap: measured best for this two-stream copy (6.5 TB/s; the
+  // fused-step kernel's own shape, one wavefront per workgroup with 16 per CU, copies at 5.8 TB/s)
   const uint64_t grid = (n16 + 255) / 256;
   hipLaunchKernelGGL(copy_kernel, dim3(static_cast<uint32_t>(grid)), dim3(256), 0, s, static_cast<f4*>(dst),
                      static_cast<const f4*>(src), n16);

@@ -106,9 +106,11 @@ def test_selector_indices_and_masks_are_bit_exact(d, block, R_step, R_reset):
 
 
 # ---------------------------------------------------------------------------- named workloads
-def test_tiny_workload_100_steps():
+@pytest.mark.parametrize("tuning", [None, {6: 0}, {4: 0}, {4: 0, 6: 0}], ids=["fused-reset", "separate-reset",
+                                                                              "lane-walks-workers", "lane-walks-separate"])
+def test_tiny_workload_100_steps(tuning):
     wl = I.WORKLOADS["tiny"]
-    diff = run_pair(wl, 100, check_every=20)
+    diff = run_pair(wl, 100, check_every=20, tuning=tuning)
     assert diff == 0, f"{diff} elements not bit-identical"
 
 
@@ -166,6 +168,16 @@ def test_misaligned_base_pointers():
 def test_implementation_two_without_residual_buffer():
     wl = _wl(d=20000, W=8, steps=16)
     assert run_pair(wl, 16, with_error=False) == 0
+    assert run_pair(wl, 16, with_error=False, tuning={6: 0}) == 0
+    assert run_pair(_wl(d=20000, W=5, R_step=2, R_reset=2, H=1), 8, with_error=False) == 0
+
+
+def test_blocks_chosen_by_both_compressors_at_once():
+    # R_step = R_reset = 2 with H = 1: a quarter of the blocks is in both choices at every iteration
+    for kw in (dict(), dict(W=3), dict(block=6), dict(momentum=0.0)):
+        wl = _wl(d=30000, R_step=2, R_reset=2, H=1, **kw)
+        assert run_pair(wl, 10) == 0
+        assert run_pair(wl, 10, tuning={4: 0}) == 0
 
 
 def test_no_momentum_buffer_is_algorithm_2():
@@ -177,7 +189,7 @@ def test_no_momentum_buffer_is_algorithm_2():
 @pytest.mark.parametrize("tuning", [{4: 0}, {4: 0, 0: 1}, {4: 0, 0: 7}, {4: 0, 1: 0}, {4: 0, 2: 1}, {4: 0, 2: 2},
                                     {4: 0, 2: 8}, {4: 0, 0: 3, 1: 0, 2: 8}, {4: 0, 3: 64}, {4: 0, 3: 1024},
                                     {4: 1, 5: 2}, {4: 1, 5: 4, 3: 512}, {4: 2}, {4: 2, 5: 2, 3: 128}, {4: 3},
-                                    {4: 3, 3: 64, 5: 4}, {1: 0}, {1: 2}, {1: 3}, {3: 64}, {3: 1024}])
+                                    {4: 3, 3: 64, 5: 4}, {1: 0}, {1: 2}, {1: 3}, {3: 256}, {3: 1024}, {6: 0}, {6: 0, 4: 0}])
 def test_results_do_not_depend_on_launch_shape(tuning):
     wl = _wl(d=30000, W=8, steps=8)
     assert run_pair(wl, 8, tuning=tuning) == 0
@@ -324,6 +336,12 @@ def test_profile_counters_and_copy_probe():
     opt = B.CSER(cfg, I.initial_model(wl, dev))
     B.cser_profile_enable(opt.ctx, True)
     g = I.gradient(wl, 1, dev)
+    for _ in range(6):
+        opt.step(g)
+    assert B.cser_profile_read(opt.ctx, 0)[1] == 6
+    assert B.cser_profile_read(opt.ctx, 1)[1] == 0      # resets ran inside the fused-step kernel
+    B.cser_profile_clear(opt.ctx)
+    B.cser_set_tuning(opt.ctx, 6, 0)                     # separate reset kernel
     for _ in range(6):
         opt.step(g)
     ms0, n0 = B.cser_profile_read(opt.ctx, 0)
