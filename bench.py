@@ -49,7 +49,7 @@ def read_traffic(workload):
     return float(m.group(1)) if m else None
 
 
-def cpu_baseline(wl, seconds_target=15.0):
+def cpu_baseline(wl, variant_e=True, variant_m=True):
     """The oracle as it stands, one host thread, on a slice of the workload's blocks."""
     import numpy as np
     from oracle import reference as R
@@ -59,8 +59,8 @@ def cpu_baseline(wl, seconds_target=15.0):
     rng = np.random.default_rng(wl.seed)
     x0 = (rng.standard_normal(ncols) * np.sqrt(wl.x_var)).astype(np.float32)
     g = [(rng.standard_normal((wl.W, ncols)) * np.sqrt(wl.g_var)).astype(np.float32) for _ in range(2)]
-    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, x0,
-                     dtype=np.float32, b0=0, b1=nb)
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum if variant_m else 0.0,
+                     wl.seed, x0, dtype=np.float32, b0=0, b1=nb, with_error=variant_e)
     t0 = time.perf_counter()
     for t in range(steps):
         o.step(g[t & 1])
@@ -71,39 +71,23 @@ def cpu_baseline(wl, seconds_target=15.0):
             "host_cpus": os.cpu_count()}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="large_cnn")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
-                    help="cser_set_tuning(key, value) before the run (launch-shape experiments)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (all W worker states are resident on it and the worker "
-                 "average is a reduction over rows, not a collective); --gpus must be 1")
-
+def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, variant_m=True):
+    """Time `steps` calls of cser_step on one workload; returns the fields of the JSON line."""
     import torch
     from paper_2007_13221_amd import binding as B
     from paper_2007_13221_amd import inputs as I
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
-    named = dict(I.WORKLOADS)
-    named.update({w.name: w for w in I.sweep_workloads()})
-    wl = named[args.workload]
-    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
-    opt = B.CSER(cfg, I.initial_model(wl, dev))
-    for item in args.tune:
+    momentum = wl.momentum if variant_m else 0.0
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=variant_e, with_momentum=variant_m)
+    for item in tune:
         key, value = item.split("=")
         B.cser_set_tuning(opt.ctx, int(key), int(value))
     grads = [I.gradient(wl, t, dev) for t in (1, 2)]   # generated outside every timed region
     torch.cuda.synchronize()
 
-    for t in range(args.warmup):
+    for t in range(warmup):
         opt.step(grads[t & 1])
     torch.cuda.synchronize()
 
@@ -112,7 +96,7 @@ def main():
     t_first = B.cser_get_step(opt.ctx) + 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t in range(args.steps):
+    for t in range(steps):
         opt.step(grads[t & 1])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -126,50 +110,54 @@ def main():
     total_step_bytes = 0
     total_reset_bytes = 0
     resets = 0
-    for t in range(t_first, t_first + args.steps):
+    for t in range(t_first, t_first + steps):
         _, mask = B.cser_select_blocks(opt.ctx, 0, t)
-        total_step_bytes += step_bytes(wl, chosen_columns(wl, mask))
+        total_step_bytes += step_bytes(wl, chosen_columns(wl, mask), variant_e, variant_m)
         if wl.H and t % wl.H == 0:
             resets += 1
             if not resets_fused:
                 _, rmask = B.cser_select_blocks(opt.ctx, 1, t)
-                total_reset_bytes += 16 * wl.W * chosen_columns(wl, rmask)
-    bytes_per_launch = total_step_bytes / args.steps
+                total_reset_bytes += (16 if variant_e else 8) * wl.W * chosen_columns(wl, rmask)
+    bytes_per_launch = total_step_bytes / steps
     kernel_ms = step_ms / max(step_launches, 1)
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
 
-    # practical ceiling: a plain 128-bit copy kernel over buffers of the same total size class
-    n_copy = wl.W * wl.ld * 4
-    src, dst = opt.m, torch.empty_like(opt.m)
-    for _ in range(3):
-        B.cser_copy_probe(dst, src, n_copy)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for _ in range(20):
-        B.cser_copy_probe(dst, src, n_copy)
-    ev1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 2 * n_copy * 20 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-    del dst
+    copy_gbps = None
+    if with_copy:
+        # a plain 128-bit copy kernel over buffers of the same size, for comparison and counter calibration
+        n_copy = wl.W * wl.ld * 4
+        src, dst = opt.x, torch.empty_like(opt.x)
+        for _ in range(3):
+            B.cser_copy_probe(dst, src, n_copy)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(20):
+            B.cser_copy_probe(dst, src, n_copy)
+        ev1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 2 * n_copy * 20 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        del dst
 
+    kind = ("implementation I" if variant_e else "implementation II (no e)") + ("" if variant_m else ", no momentum buffer")
     out = {
         "metric": "CSER step param-elements/s and achieved HBM GB/s (% of peak) at d=25.6M, W=8",
-        "value": wl.d * args.steps / elapsed,
+        "value": wl.d * steps / elapsed,
         "unit": "param-elements/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": elapsed * 1e3 / args.steps,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": elapsed * 1e3 / steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: d={wl.d}, W={wl.W}, block={wl.block}, R_step={wl.R_step}, "
-                               f"R_reset={wl.R_reset}, H={wl.H}, lr={wl.lr}, momentum={wl.momentum}, "
-                               f"g~N(0,{wl.g_var}), seed={wl.seed}; steps t={t_first}..{t_first + args.steps - 1}",
+                               f"R_reset={wl.R_reset}, H={wl.H}, lr={wl.lr}, momentum={momentum}, "
+                               f"g~N(0,{wl.g_var}), seed={wl.seed}; steps t={t_first}..{t_first + steps - 1}; {kind}",
                    "resident": "x, e, m [W][ld] fp32 + 2 rotating g buffers", "ld": wl.ld},
-        "worker_elements_per_s": wl.W * wl.d * args.steps / elapsed,
+        "worker_elements_per_s": wl.W * wl.d * steps / elapsed,
         "whole_path_GBps": (total_step_bytes + total_reset_bytes) / elapsed / 1e9,
         "whole_path_frac_of_peak": (total_step_bytes + total_reset_bytes) / elapsed / 1e9 / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": "cser_step_rows_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": read_traffic(wl.name),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": read_traffic(wl.name) if (variant_e and variant_m) else None,
                      "bytes_per_launch": bytes_per_launch, "ms_per_launch": kernel_ms, "launches": step_launches},
         "resets": {"in_timed_region": resets, "fused_into_step_kernel": resets_fused,
                    "separate_kernel_launches": reset_launches,
@@ -177,8 +165,54 @@ def main():
         "copy_kernel_GBps": copy_gbps,
     }
     opt.close()
+    del opt, grads
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="large_cnn")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", choices=["I", "II", "I-nomomentum", "II-nomomentum"], default="I",
+                    help="I: x, e, m (Algorithm 3); II: no residual buffer (Appendix A.4); -nomomentum: beta = 0, no m")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the one headline line: one compact line per point of the 40-point compression "
+                         "sweep at the large-CNN size (50 steps each)")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="cser_set_tuning(key, value) before the run (launch-shape experiments)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (all W worker states are resident on it and the worker "
+                 "average is a reduction over rows, not a collective); --gpus must be 1")
+
+    import torch
+    from paper_2007_13221_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    variant_e = not args.variant.startswith("II")
+    variant_m = not args.variant.endswith("nomomentum")
+    if args.sweep:
+        for wl in I.sweep_workloads():
+            r = run_workload(wl, wl.steps, 5, args.tune, with_copy=False, variant_e=variant_e, variant_m=variant_m)
+            print(json.dumps({"workload": wl.name, "R_step": wl.R_step, "block": wl.block, "H": wl.H,
+                              "steps": wl.steps, "ms_per_step": round(r["ms_per_step"], 4),
+                              "G_param_elements_per_s": round(r["value"] / 1e9, 2),
+                              "step_kernel_ms": round(r["roofline"]["ms_per_launch"], 4),
+                              "step_kernel_GBps": round(r["roofline"]["achieved"], 1),
+                              "step_kernel_frac_of_peak": round(r["roofline"]["frac"], 3),
+                              "whole_path_GBps": round(r["whole_path_GBps"], 1)}), flush=True)
+        return
+    named = dict(I.WORKLOADS)
+    named.update({w.name: w for w in I.sweep_workloads()})
+    wl = named[args.workload]
+    out = run_workload(wl, args.steps, args.warmup, args.tune, variant_e=variant_e, variant_m=variant_m)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl)
+        out["cpu_baseline"] = cpu_baseline(wl, variant_e, variant_m)
     print(json.dumps(out))
 
 

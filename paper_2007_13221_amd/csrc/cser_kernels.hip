@@ -167,6 +167,47 @@ __device__ __forceinline__ void step_columns(const StepParams& a, uint64_t col, 
   }
 }
 
+// Chosen block, W <= 8: the same arithmetic as the chosen branch of step_columns, but g, m and x of all
+// workers are requested in one go and held in registers, so the lane waits for memory once
+// instead of four times (loads of absent workers i >= W are skipped, their slots unused).
+template <int V, bool NT, bool HAS_M>
+__device__ __forceinline__ void step_chosen_up_to_8(const StepParams& a, uint64_t col) {
+  Pack<V> g[8], m[8], x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (static_cast<uint32_t>(i) < a.W) {
+      const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
+      g[i] = load_pack<V, NT>(a.g + off);
+      if constexpr (HAS_M) m[i] = load_pack<V, NT>(a.m + off);
+      x[i] = load_pack<V, NT>(a.x + off);
+    }
+  }
+  Pack<V> sum;
+#pragma unroll
+  for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (static_cast<uint32_t>(i) < a.W) {
+      const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g[i], m[i]);
+      if constexpr (HAS_M) store_pack<V, NT>(a.m + static_cast<uint64_t>(i) * a.ld + col, m[i]);
+#pragma unroll
+      for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + p.v[c];   // workers in order i = 0, 1, ...
+    }
+  }
+  const float n = static_cast<float>(a.W);
+  Pack<V> pbar;
+#pragma unroll
+  for (int c = 0; c < V; ++c) pbar.v[c] = sum.v[c] / n;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (static_cast<uint32_t>(i) < a.W) {
+#pragma unroll
+      for (int c = 0; c < V; ++c) x[i].v[c] = x[i].v[c] - pbar.v[c];
+      store_pack<V, NT>(a.x + static_cast<uint64_t>(i) * a.ld + col, x[i]);
+    }
+  }
+}
+
 // Reset iterations (t mod H = 0) with the reset fused into the step: the V columns at `col` belong
 // to a block C_reset chose, so after the step's own update the error reset follows at once,
 //   ebar = (e'_0 + ... + e'_{W-1}) / W ;  x_i <- (x'_i - e'_i) + ebar ;  e_i <- +0
@@ -332,7 +373,10 @@ __global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint
     for (int c = 0; c < C; ++c) {
       const uint64_t col = static_cast<uint64_t>(q[c]) * 4;
       if (reset_chosen[c]) step_and_reset_columns<4, HAS_E, HAS_M>(a, col, chosen[c]);
-      else if (chosen[c]) step_columns<4, 4, NTL && NTS, HAS_E, HAS_M>(a, col, true);
+      else if (chosen[c]) {
+        if (a.W <= 8) step_chosen_up_to_8<4, NTL && NTS, HAS_M>(a, col);
+        else step_columns<4, 4, NTL && NTS, HAS_E, HAS_M>(a, col, true);
+      }
     }
   }
 }
@@ -464,15 +508,18 @@ __global__ __launch_bounds__(256) void grbs_select_kernel(uint32_t seed_lo, uint
   if (chosen && idx != nullptr) idx[v] = b;
 }
 
-// The same choice from the other side: thread j < k evaluates pi(j) with the forward network and
-// marks that block in a mask that was zeroed beforehand.  k evaluations instead of B, so this is the
-// cheaper form whenever the compressor keeps less than half of the blocks; both forms give the same
-// mask because pi is a bijection.
+// The same choice from the other side: a thread evaluates pi(j) with the forward network and writes
+// `value` into that block's byte of a mask that was filled with the opposite value beforehand.
+// Draws j in [0, k) with value 1 on a zeroed mask mark the chosen blocks (k evaluations); draws j in
+// [k, B) with value 0 on a mask of ones clear the unchosen ones (B - k evaluations).  Whichever is
+// smaller costs less than the B evaluations of grbs_select_kernel; all forms give the same mask
+// because pi is a bijection.  idx (may be null) is only meaningful for the first form.
 __global__ __launch_bounds__(256) void grbs_scatter_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
-                                                            uint64_t t0, uint64_t t_stride, uint32_t B, uint32_t k,
-                                                            uint32_t half_bits, uint8_t* mask, uint32_t* idx) {
-  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= k) return;
+                                                            uint64_t t0, uint64_t t_stride, uint32_t B, uint32_t j_begin,
+                                                            uint32_t j_end, uint8_t value, uint32_t half_bits,
+                                                            uint8_t* mask, uint32_t* idx) {
+  const uint32_t j = j_begin + blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= j_end) return;
   const uint64_t t = t0 + blockIdx.y * t_stride;
   const uint32_t t_lo = static_cast<uint32_t>(t), t_hi = static_cast<uint32_t>(t >> 32);
   mask += static_cast<uint64_t>(blockIdx.y) * B;
@@ -492,17 +539,18 @@ __global__ __launch_bounds__(256) void grbs_scatter_kernel(uint32_t seed_lo, uin
     if (v < B) break;
   }
   if (v < B) {   // always true (see the bound above); keeps a write in range whatever happens
-    mask[v] = 1;
+    mask[v] = value;
     if (idx != nullptr) idx[j] = v;
   }
 }
 
-__global__ __launch_bounds__(256) void fill_bytes_zero_kernel(uint8_t* p, uint64_t n) {
+__global__ __launch_bounds__(256) void fill_bytes_kernel(uint8_t* p, uint64_t n, uint8_t value) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
   const uint64_t n4 = n / 4;   // p comes from hipMalloc: 4-byte aligned
   uint32_t* p4 = reinterpret_cast<uint32_t*>(p);
-  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) p4[i] = 0u;
-  if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) p[n4 * 4 + threadIdx.x] = 0;
+  const uint32_t word = value * 0x01010101u;
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) p4[i] = word;
+  if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) p[n4 * 4 + threadIdx.x] = value;
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, uint64_t n) {
@@ -604,18 +652,21 @@ hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint6
                            uint32_t k, uint8_t* mask, uint32_t* idx, hipStream_t s) {
   if (count == 0) return hipSuccess;
   const uint32_t seed_lo = static_cast<uint32_t>(seed), seed_hi = static_cast<uint32_t>(seed >> 32);
-  if (static_cast<uint64_t>(k) * 2 < B) {
-    // few blocks kept: zero the masks, then one forward evaluation per kept block
+  const bool few_kept = static_cast<uint64_t>(k) * 2 < B;
+  if (few_kept || idx == nullptr) {
+    // fill the masks with "unchosen" (few kept) or "chosen" (most kept), then one forward evaluation per exception
+    const uint8_t fill = few_kept ? 0 : 1;
+    const uint32_t j_begin = few_kept ? 0u : k, j_end = few_kept ? k : B;
     const uint64_t bytes = static_cast<uint64_t>(count) * B;
     uint64_t fill_grid = (bytes / 4 + 255) / 256;
     if (fill_grid > 4096) fill_grid = 4096;
     if (fill_grid == 0) fill_grid = 1;
-    hipLaunchKernelGGL(fill_bytes_zero_kernel, dim3(static_cast<uint32_t>(fill_grid)), dim3(256), 0, s, mask, bytes);
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3(static_cast<uint32_t>(fill_grid)), dim3(256), 0, s, mask, bytes, fill);
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess || k == 0) return err;
-    const dim3 grid((k + 255u) / 256u, count);
-    hipLaunchKernelGGL(grbs_scatter_kernel, grid, dim3(256), 0, s, seed_lo, seed_hi, stream_id, t0, t_stride, B, k,
-                       half_bits_for(B), mask, idx);
+    if (err != hipSuccess || j_end == j_begin) return err;
+    const dim3 grid((j_end - j_begin + 255u) / 256u, count);
+    hipLaunchKernelGGL(grbs_scatter_kernel, grid, dim3(256), 0, s, seed_lo, seed_hi, stream_id, t0, t_stride, B, j_begin,
+                       j_end, static_cast<uint8_t>(1 - fill), half_bits_for(B), mask, few_kept ? idx : nullptr);
     return hipGetLastError();
   }
   const dim3 grid((B + 255u) / 256u, count);
