@@ -95,8 +95,8 @@ def run_sliced(wl, steps, check_mean_model=True, forced_reset=False):
     opt.close()
 
 
-def test_large_cnn_full_size_34_steps_with_reset():
-    run_sliced(I.WORKLOADS["large_cnn"], 34)
+def test_large_cnn_full_size_100_steps_with_three_resets():
+    run_sliced(I.WORKLOADS["large_cnn"], 100)
 
 
 @pytest.mark.parametrize("R_step,block,H", [(2, 64, 4), (1024, 4096, 4), (8, 256, 4), (32, 1024, 4)])
