@@ -254,6 +254,31 @@ def test_forced_reset_and_resume_from_checkpoint():
     opt.close()
 
 
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        d = int(rng.choice([1, 2, 3, 5, 63, 64, 65, 257, 1000, 1023, 4096, 5003, 20011]))
+        block = int(rng.choice([1, 2, 3, 4, 6, 8, 16, 64, 100, 256, 1000, 4096]))
+        momentum = float(rng.choice([0.0, 0.5, 0.9]))
+        cases.append(dict(
+            d=d, W=int(rng.integers(1, 13)), block=block, R_step=int(rng.choice([0, 1, 2, 3, 5, 16, 1000])),
+            R_reset=int(rng.choice([1, 2, 3, 7, 64])), H=int(rng.choice([0, 1, 2, 3, 5])), momentum=momentum,
+            lr=float(rng.choice([0.1, 0.01, 1.0])), seed=int(rng.integers(0, 2**62)),
+            ld=int(rng.choice([d, -(-d // 4) * 4, -(-d // 64) * 64, -(-d // 1024) * 1024])),
+            with_error=bool(rng.integers(0, 2)), with_momentum=bool(momentum != 0.0 or rng.integers(0, 2)),
+            tuning=[None, {4: 0}, {4: 2, 5: 2}, {6: 0}, {3: 256, 5: 4}, {4: 3, 1: 0}][int(rng.integers(0, 6))]))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(48, 20200725), ids=lambda c: f"d{c['d']}-W{c['W']}-b{c['block']}")
+def test_randomly_drawn_configurations(case):
+    wl = _wl(d=case["d"], W=case["W"], block=case["block"], R_step=case["R_step"], R_reset=case["R_reset"], H=case["H"],
+             momentum=case["momentum"], lr=case["lr"], seed=case["seed"])
+    assert run_pair(wl, 7, ld=case["ld"], with_error=case["with_error"], with_momentum=case["with_momentum"],
+                    tuning=case["tuning"]) == 0
+
+
 def test_step_counter_jumps_across_the_mask_window():
     """C_step's masks are drawn 32 iterations per selector launch; moving t backwards, forwards and
     across window edges must still use the mask of the iteration actually being run."""
