@@ -136,7 +136,8 @@ int cser_profile_clear(cser_ctx* ctx);
  *          columns, tiles vary fastest with the workgroup id; 2 = row-split, workers vary fastest;
  *          0 = a lane walks all W workers for its 4 columns
  *   key 3  workgroup size: 64 (default), 128, 256, 512 or 1024
- *   key 1  1 (default) = non-temporal loads/stores, 0 = ordinary
+ *   key 1  -1 (default) = non-temporal loads/stores unless all state fits 256 MiB, 1 = always, 0 = never,
+ *          2 / 3 = loads only / stores only
  *   key 5  row-split variants: 4-column groups per lane, 1 (default), 2 or 4
  *   key 6  1 (default) = on iterations with t mod H = 0 the error reset runs inside the fused-step kernel
  *          (x and e of the reset blocks make one trip instead of two); 0 = separate reset kernel

@@ -370,7 +370,7 @@ int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
       ctx->tuning.wg_cap = value;
       return CSER_OK;
     case 1:
-      if (value < 0 || value > 3) return CSER_EINVAL;
+      if (value < -1 || value > 3) return CSER_EINVAL;
       ctx->tuning.nontemporal = static_cast<int>(value);
       return CSER_OK;
     case 2:

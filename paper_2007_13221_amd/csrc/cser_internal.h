@@ -38,7 +38,7 @@ struct ResetParams {
 
 struct Tuning {
   int64_t wg_cap = 0;   // 0: one 4-column group per lane; > 0: at most this many workgroups
-  int nontemporal = 1;  // 0 none, 1 loads and stores, 2 loads only, 3 stores only (variant 0: zero / non-zero)
+  int nontemporal = -1;  // -1 by working-set size, 0 none, 1 loads and stores, 2 loads only, 3 stores only (variant 0: zero / non-zero)
   int batch = 4;        // workers whose loads are issued together
   int threads = 64;     // workgroup size of the fused-step kernel (one wavefront: measured best)
   int variant = 1;      // 0: a lane walks all workers; row-split: 1 tiles fastest, 2 workers fastest, 3 per-XCD sweeps
