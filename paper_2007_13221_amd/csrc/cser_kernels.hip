@@ -2,19 +2,23 @@
 //
 //   grbs_select_kernel      the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3),
 //   grbs_scatter_kernel     from the blocks' side (inverse permutation) or from the draws' side (forward)
-//   cser_step_rows_kernel   Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass
+//   cser_step_rows_kernel   Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass, and on
+//                           reset iterations the error reset as well
 //   cser_step_kernel        the same, one lane per column group walking all workers (element-wise
 //                           fallback for unaligned layouts; also a measured alternative)
-//   cser_reset_kernel       the error-reset branch of Algorithm 3 (PSync(e, C_reset) and the x correction)
+//   cser_reset_kernel       the error-reset branch of Algorithm 3 on its own (PSync(e, C_reset), x correction)
 //
 // The update is a pure stream over HBM (about 6 flops per 28 bytes), so there is no matrix-core
 // work here and nothing to stage in LDS.  States are worker-major rows [W][ld].  On a block that
 // C_step did not choose, every worker's update is independent, so the default kernel gives each
-// workgroup ONE worker's row over a tile of columns: 4 load streams and 3 store streams of
-// 128-bit non-temporal accesses, consecutive workgroups on consecutive tiles.  Only the chosen
-// blocks (1 / R_step of them) need the worker mean; there a lane owns 4 columns and walks the
-// worker axis itself, so the W-way sum is a private, fixed-order chain of adds in registers -- no
-// LDS, no cross-lane traffic, and the same order as a sequential evaluation.
+// workgroup -- a single wavefront -- ONE worker's row over 256 columns: 4 load streams and 3 store
+// streams of 128-bit accesses, 1 KiB per stream, consecutive workgroups on consecutive tiles.
+// Only the chosen blocks (1 / R_step of them) need the worker mean; there a lane owns 4 columns and
+// walks the worker axis itself, so the W-way sum is a private, fixed-order chain of adds in
+// registers -- no LDS, no cross-lane traffic, and the same order as a sequential evaluation.
+// What the memory system rewards, all measured: one worker per workgroup rather than all workers
+// per lane, 1 KiB tiles, rows that start on 4 KiB boundaries, non-temporal accesses once the state
+// exceeds the last-level cache, and no more than about 16-20 resident wavefronts per CU.
 //
 // Build with -ffp-contract=off: every fused multiply-add below is written out, nothing else fuses.
 

@@ -148,6 +148,10 @@ def _wl(**kw):
     dict(d=70000, block=4096, R_step=2),      # block larger than a workgroup's columns
     dict(momentum=0.0),
     dict(lr=0.0),
+    dict(W=33, d=3000, R_step=2),             # more workers than the in-register chosen-block path holds
+    dict(W=64, d=2000, R_step=2, R_reset=2, H=2),
+    dict(d=50000, block=65536, R_step=1, R_reset=1, H=2),   # a single block, always chosen by both compressors
+    dict(d=50000, block=65536, R_step=0, R_reset=1, H=2),
 ])
 def test_edge_cases_match_bit_for_bit(kw):
     wl = _wl(**kw)
