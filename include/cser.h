@@ -112,6 +112,21 @@ int cser_select_blocks(cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host,
 /* Sizes derived from the configuration: B, k_step = ceil(B/R_step), k_reset = ceil(B/R_reset). */
 int cser_block_counts(const cser_ctx* ctx, uint64_t* B, uint32_t* k_step, uint32_t* k_reset);
 
+/*
+ * The special cases of Appendix A.1 as settings of a configuration (host only, no device work):
+ *   cser_preset_csea     C_step(v) = 0 and H = 1: SGD with error assimilation (CSEA); R_reset is its one compressor
+ *   cser_preset_cser_pl  C_step(v) = 0: partial-local SGD (CSER-PL); with R_reset = 1 it is local SGD with period H
+ * Both only overwrite R_step (and H); every other field is left as the caller set it.
+ */
+int cser_preset_csea(cser_config* cfg);
+int cser_preset_cser_pl(cser_config* cfg);
+
+/*
+ * Overall compression ratio of a configuration, Section 5.1:  R = 1 / (1/R_step + 1/(R_reset * H)),
+ * with 1/R_step = 0 for R_step = 0 and the second term 0 for H = 0.  *ratio = +inf if nothing is ever sent.
+ */
+int cser_overall_ratio(const cser_config* cfg, double* ratio);
+
 /* Learning-rate schedules (Section 5.1): takes effect from the next cser_step. */
 int cser_set_lr(cser_ctx* ctx, float lr);
 

@@ -15,6 +15,7 @@ LIBRARY = os.path.join(_HERE, "libcser_hip.so")
 CSER_OK, CSER_EINVAL, CSER_EALIGN, CSER_ENOMEM, CSER_EHIP, CSER_ERANGE = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("cser_create", "cser_step", "cser_error_reset", "cser_destroy", "cser_select_blocks",
+           "cser_preset_csea", "cser_preset_cser_pl", "cser_overall_ratio",
            "cser_block_counts", "cser_set_lr", "cser_get_step", "cser_set_step", "cser_profile_enable",
            "cser_profile_read", "cser_profile_clear", "cser_set_tuning", "cser_copy_probe", "cser_strerror",
            "cser_last_hip_error")
@@ -55,6 +56,9 @@ def _lib():
         L.cser_destroy.argtypes = [vp]
         L.cser_select_blocks.argtypes = [vp, ctypes.c_int, u64, vp, vp, ctypes.POINTER(u32)]
         L.cser_block_counts.argtypes = [vp, ctypes.POINTER(u64), ctypes.POINTER(u32), ctypes.POINTER(u32)]
+        L.cser_preset_csea.argtypes = [ctypes.POINTER(cser_config)]
+        L.cser_preset_cser_pl.argtypes = [ctypes.POINTER(cser_config)]
+        L.cser_overall_ratio.argtypes = [ctypes.POINTER(cser_config), ctypes.POINTER(ctypes.c_double)]
         L.cser_set_lr.argtypes = [vp, ctypes.c_float]
         L.cser_get_step.argtypes = [vp, ctypes.POINTER(u64)]
         L.cser_set_step.argtypes = [vp, u64]
@@ -135,6 +139,22 @@ def cser_select_blocks(ctx, which, t):
            "cser_select_blocks")
     assert kout.value == k
     return idx[:k], mask
+
+
+def cser_preset_csea(cfg: cser_config) -> cser_config:
+    _check(_lib().cser_preset_csea(ctypes.byref(cfg)), "cser_preset_csea")
+    return cfg
+
+
+def cser_preset_cser_pl(cfg: cser_config) -> cser_config:
+    _check(_lib().cser_preset_cser_pl(ctypes.byref(cfg)), "cser_preset_cser_pl")
+    return cfg
+
+
+def cser_overall_ratio(cfg: cser_config) -> float:
+    r = ctypes.c_double()
+    _check(_lib().cser_overall_ratio(ctypes.byref(cfg), ctypes.byref(r)), "cser_overall_ratio")
+    return r.value
 
 
 def cser_set_lr(ctx, lr):

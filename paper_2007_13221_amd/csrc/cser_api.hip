@@ -317,6 +317,28 @@ int cser_block_counts(const cser_ctx* ctx, uint64_t* B, uint32_t* k_step, uint32
   return CSER_OK;
 }
 
+int cser_preset_csea(cser_config* cfg) {
+  if (!cfg) return CSER_EINVAL;
+  cfg->R_step = 0;
+  cfg->H = 1;
+  return CSER_OK;
+}
+
+int cser_preset_cser_pl(cser_config* cfg) {
+  if (!cfg) return CSER_EINVAL;
+  cfg->R_step = 0;
+  return CSER_OK;
+}
+
+int cser_overall_ratio(const cser_config* cfg, double* ratio) {
+  if (!cfg || !ratio || cfg->R_reset == 0) return CSER_EINVAL;
+  double sent = 0.0;   // fraction of the elements sent per iteration
+  if (cfg->R_step > 0) sent += 1.0 / static_cast<double>(cfg->R_step);
+  if (cfg->H > 0) sent += 1.0 / (static_cast<double>(cfg->R_reset) * static_cast<double>(cfg->H));
+  *ratio = sent > 0.0 ? 1.0 / sent : HUGE_VAL;
+  return CSER_OK;
+}
+
 int cser_set_lr(cser_ctx* ctx, float lr) {
   if (!ctx || !std::isfinite(lr)) return CSER_EINVAL;
   ctx->cfg.lr = lr;

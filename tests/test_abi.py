@@ -62,3 +62,25 @@ def test_create_rejects_null_and_misaligned_pointers():
     assert B._lib().cser_create(None, 0x1000, 0x1000, 0x1000, None, ctypes.byref(out)) == B.CSER_EINVAL
     assert B._lib().cser_step(None, 0x1000, None) == B.CSER_EINVAL
     assert B._lib().cser_error_reset(None, None) == B.CSER_EINVAL
+
+
+def test_overall_ratio_matches_the_printed_table4_rows():
+    """Section 5.1's formula through the C ABI on the ten CSER rows of Table 4 (tests/golden)."""
+    rows = [tuple(int(v) for v in l.split()) for l in open(os.path.join(ROOT, "tests", "golden", "table4_cser_rows.txt"))
+            if l.strip() and l[0] != "#"]
+    assert len(rows) == 10
+    for overall, r_step, r_reset, H in rows:
+        cfg = B.make_config(1000, 8, 10, r_step, r_reset, H, 0.1, 0.9, 0)
+        assert B.cser_overall_ratio(cfg) == pytest.approx(overall, rel=1e-12)
+    # the large workload mirrors the 256x row's pattern with R_step halved: 1 / (1/256 + 1/512) = 170.67
+    assert B.cser_overall_ratio(B.make_config(1000, 8, 10, 256, 16, 32, 0.1, 0.9, 0)) == pytest.approx(512 / 3)
+
+
+def test_presets_of_the_special_cases():
+    cfg = B.cser_preset_csea(B.make_config(1000, 8, 10, 64, 4, 16, 0.1, 0.0, 0))
+    assert (cfg.R_step, cfg.H, cfg.R_reset) == (0, 1, 4) and B.cser_overall_ratio(cfg) == 4.0   # CSEA: R = R_C1
+    cfg = B.cser_preset_cser_pl(B.make_config(1000, 8, 10, 64, 4, 16, 0.1, 0.0, 0))
+    assert (cfg.R_step, cfg.H, cfg.R_reset) == (0, 16, 4) and B.cser_overall_ratio(cfg) == 64.0  # CSER-PL: R_C1 * H
+    cfg = B.make_config(1000, 8, 10, 0, 4, 0, 0.1, 0.0, 0)
+    assert B.cser_overall_ratio(cfg) == float("inf")
+    assert B._lib().cser_preset_csea(None) == B.CSER_EINVAL

@@ -336,6 +336,37 @@ def test_steps_issued_on_alternating_streams():
     opt.close()
 
 
+def test_csea_and_cser_pl_presets_against_their_algorithm_boxes():
+    """Independent of the oracle's Algorithm 3: the presets of Appendix A.1 run on the GPU and are compared with
+    numpy float64 re-codings of the CSEA and CSER-PL boxes (tests/_np_models.py), to fp32 rounding."""
+    from tests import _np_models as M
+    dev = torch.device("cuda:0")
+    d, W, block, R_reset, T, lr, seed = 3000, 4, 8, 4, 12, 0.1, 99
+    Bn = -(-d // block)
+    rng = np.random.default_rng(3)
+    x0 = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    grads = [(rng.standard_normal((W, d)) * 0.1).astype(np.float32) for _ in range(T)]
+    masks = {t: R.select_blocks(seed, 1, t, Bn, R.blocks_kept(Bn, R_reset))[1] for t in range(1, T + 1)}
+    lr32 = float(np.float32(lr))
+    for preset, H, expect in (
+            (B.cser_preset_csea, 7, lambda: M.csea_impl1(x0, [g.astype(np.float64) for g in grads], masks, lr32, block)),
+            (B.cser_preset_cser_pl, 3, lambda: M.cser_pl_impl1(x0, [g.astype(np.float64) for g in grads], masks, 3, lr32, block))):
+        cfg = preset(B.make_config(d, W, block, 64, R_reset, H, lr, 0.0, seed, ld=3072))
+        x = torch.zeros(W, 3072, device=dev)
+        x[:, :d] = torch.from_numpy(x0).to(dev)
+        opt = B.CSER(cfg, x, with_momentum=False)
+        g = torch.zeros(W, 3072, device=dev)
+        for t in range(T):
+            g[:, :d] = torch.from_numpy(grads[t]).to(dev)
+            opt.step(g)
+        torch.cuda.synchronize()
+        want_x, want_e = expect()
+        np.testing.assert_allclose(opt.x[:, :d].cpu().numpy(), want_x, rtol=0, atol=2e-6)
+        np.testing.assert_allclose(opt.e[:, :d].cpu().numpy(), want_e, rtol=0, atol=2e-6)
+        assert np.abs(want_e).max() > 1e-3
+        opt.close()
+
+
 def test_gpu_run_stays_within_rounding_of_the_float64_oracle():
     """Independent of the shared fp32 contract: against the oracle in double precision the fp32 states
     differ by accumulated rounding only (about one rounding of 2^-24 |value| per statement and step)."""
