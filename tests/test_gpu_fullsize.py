@@ -109,3 +109,9 @@ def test_transformer_sized_stress_with_forced_reset():
     # 20 steps are fewer than H = 64, so the reset is forced once at the end, as the workload prescribes
     wl = I.WORKLOADS["transformer"]
     run_sliced(wl, 6, check_mean_model=False, forced_reset=True)
+
+
+def test_rows_longer_than_2_pow_31_columns():
+    """Column and byte offsets beyond 32 bits: d = 2^31 + 4099 (ragged tail, d % 4 = 3), two workers, 69 GB resident."""
+    wl = I.Workload("wide", 2**31 + 4099, 2, 4096, 64, 4, 2, 0.1, 0.9, 1e-2, 1e-3, 7, 3)
+    run_sliced(wl, 3, check_mean_model=False)
