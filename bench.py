@@ -155,7 +155,7 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
         "worker_elements_per_s": wl.W * wl.d * steps / elapsed,
         "whole_path_GBps": (total_step_bytes + total_reset_bytes) / elapsed / 1e9,
         "whole_path_frac_of_peak": (total_step_bytes + total_reset_bytes) / elapsed / 1e9 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "cser_step_rows_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "cser_step_tile_kernel" if (wl.W & (wl.W - 1)) == 0 and wl.W <= 64 and not tune else "cser_step_*_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic(wl.name) if (variant_e and variant_m) else None,
                      "bytes_per_launch": bytes_per_launch, "ms_per_launch": kernel_ms, "launches": step_launches},

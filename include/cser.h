@@ -157,6 +157,8 @@ int cser_profile_clear(cser_ctx* ctx);
  *   key 6  1 (default) = on iterations with t mod H = 0 the error reset runs inside the fused-step kernel
  *          (x and e of the reset blocks make one trip instead of two); 0 = separate reset kernel
  *   key 7  bytes of (unused) dynamic LDS per workgroup, 0 .. 65536 (default 10240): caps workgroups per CU
+ *   key 8  1 (default) = for W a power of two <= 64 the blocks that need the worker mean are shared out over the W
+ *          workgroups of a tile (in-wavefront ordered sums); 0 = worker 0's workgroup walks all rows for them
  *   key 0  variant 0: workgroup cap (0 = one group per lane; n > 0 = at most n workgroups, lanes loop)
  *   key 2  variant 0: workers whose loads are issued together (1, 2, 4 or 8)
  */

@@ -2,8 +2,10 @@
 //
 //   grbs_select_kernel      the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3),
 //   grbs_scatter_kernel     from the blocks' side (inverse permutation) or from the draws' side (forward)
-//   cser_step_rows_kernel   Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass, and on
-//                           reset iterations the error reset as well
+//   cser_step_tile_kernel   Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass, and on
+//                           reset iterations the error reset as well (W a power of two <= 64: the default)
+//   cser_step_rows_kernel   the same for any W and other launch shapes (worker 0's workgroup walks all rows
+//                           of the blocks that need the worker mean)
 //   cser_step_kernel        the same, one lane per column group walking all workers (element-wise
 //                           fallback for unaligned layouts; also a measured alternative)
 //   cser_reset_kernel       the error-reset branch of Algorithm 3 on its own (PSync(e, C_reset), x correction)
@@ -13,9 +15,12 @@
 // C_step did not choose, every worker's update is independent, so the default kernel gives each
 // workgroup -- a single wavefront -- ONE worker's row over 256 columns: 4 load streams and 3 store
 // streams of 128-bit accesses, 1 KiB per stream, consecutive workgroups on consecutive tiles.
-// Only the chosen blocks (1 / R_step of them) need the worker mean; there a lane owns 4 columns and
-// walks the worker axis itself, so the W-way sum is a private, fixed-order chain of adds in
-// registers -- no LDS, no cross-lane traffic, and the same order as a sequential evaluation.
+// Only the chosen blocks (1 / R_step of them) need the worker mean.  In the default kernel the W
+// workgroups of a tile share that work: each takes 1/W of the tile's chosen column groups for all
+// workers, one worker per lane group, and the W-way sum is a fixed-order chain of wavefront
+// shuffles -- every value still makes one trip, and the order is that of a sequential evaluation.
+// In the general kernel a lane owns 4 columns and walks the worker axis itself (a private chain of
+// adds in registers).
 // What the memory system rewards, all measured: one worker per workgroup rather than all workers
 // per lane, 1 KiB tiles, rows that start on 4 KiB boundaries, non-temporal accesses once the state
 // exceeds the last-level cache, and no more than about 16-20 resident wavefronts per CU.
@@ -385,6 +390,157 @@ __global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint
   }
 }
 
+// Ordered worker sum inside one wavefront.  Lanes are laid out as (worker j, group k) = (lane / G,
+// lane % G); every lane fetches the W values of its group k with wavefront shuffles and adds them in
+// the order j = 0, 1, ..., W-1 -- the order of a sequential evaluation -- so all W lanes of a group
+// end up with the same bits.  Must be called with all 64 lanes active.
+template <int V>
+__device__ __forceinline__ Pack<V> worker_sum_in_wave(const Pack<V>& v, uint32_t W, uint32_t G, uint32_t k) {
+  Pack<V> sum;
+#pragma unroll
+  for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
+  for (uint32_t j = 0; j < W; ++j) {
+    const int src = static_cast<int>(j * G + k);
+#pragma unroll
+    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + __shfl(v.v[c], src, 64);
+  }
+  return sum;
+}
+
+// Balanced row-split kernel for W a power of two up to 64; one wavefront per workgroup, which owns
+// the pair (worker i, tile of 64 column groups = 256 columns) and plays two roles:
+//   A  lane l takes column group l of the tile in worker i's row, if its block was chosen by neither
+//      compressor: the purely local update, as in cser_step_rows_kernel;
+//   B  the tile's column groups are cut into W slices of G = 64 / W groups; this workgroup takes
+//      slice i for ALL workers: lane (j, k) holds worker j's values of group i*G + k.  For groups
+//      whose block C_step chose, pbar is the in-wavefront ordered sum over j divided by W; for groups
+//      C_reset chose on a reset iteration the error reset follows at once, from registers:
+//      ebar = ordered sum of the post-step e_j / W, x_j <- (x_j - e_j) + ebar, e_j <- +0
+//      (implementation II: x_j <- ordered sum of the post-step x_j / W).
+// Every workgroup of a tile thus does 1/W of the tile's synchronised work, whatever share of the
+// blocks is chosen, and each value is read and written exactly once.  The arithmetic and its order
+// are those of the other kernels.
+template <int NTMODE, bool HAS_E, bool HAS_M>
+__global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32_t groups, uint32_t tiles,
+                                                             uint32_t order, uint32_t log2_w) {
+  constexpr bool NTL = (NTMODE & 1) != 0, NTS = (NTMODE & 2) != 0;
+  uint32_t tile, i;
+  if (order == 1) {
+    tile = blockIdx.x >> log2_w;
+    i = blockIdx.x & (a.W - 1u);
+  } else {
+    uint32_t linear = blockIdx.x;
+    if (order == 2) {
+      const uint32_t per_xcd = gridDim.x / 8u;   // the launcher rounds the grid up to a multiple of 8
+      linear = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+      if (linear >= tiles * a.W) return;         // uniform over the workgroup
+    }
+    i = linear / tiles;
+    tile = linear - i * tiles;
+  }
+  const uint32_t lane = threadIdx.x;
+  const uint32_t groups_per_block = a.block / 4u;
+  const uint32_t G = 64u >> log2_w;              // column groups per slice
+  const uint32_t j = lane / G, k = lane - j * G; // role B: worker j, group k of slice i
+  const uint64_t tile_first = static_cast<uint64_t>(tile) * 64u;
+
+  // role A
+  const uint64_t qa = tile_first + lane;
+  const bool live_a = qa < groups;
+  const uint32_t ba = static_cast<uint32_t>(live_a ? qa : 0u) / groups_per_block;
+  const bool local_a = live_a && a.mask[ba] == 0 && (a.reset_mask == nullptr || a.reset_mask[ba] == 0);
+  // role B
+  const uint64_t qb = tile_first + static_cast<uint64_t>(i) * G + k;
+  const bool live_b = qb < groups;
+  const uint32_t bb = static_cast<uint32_t>(live_b ? qb : 0u) / groups_per_block;
+  const bool step_b = live_b && a.mask[bb] != 0;
+  const bool reset_b = live_b && a.reset_mask != nullptr && a.reset_mask[bb] != 0;
+  const bool sync_b = step_b || reset_b;
+
+  const uint64_t off_a = static_cast<uint64_t>(i) * a.ld + qa * 4u;
+  const uint64_t off_b = static_cast<uint64_t>(j) * a.ld + qb * 4u;
+  Pack<4> ga, ma, xa, ea, gb, mb, xb, eb;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    gb.v[c] = 0.0f; mb.v[c] = 0.0f; xb.v[c] = 0.0f; eb.v[c] = 0.0f;
+  }
+  if (local_a) {
+    ga = load_pack<4, NTL>(a.g + off_a);
+    if constexpr (HAS_M) ma = load_pack<4, NTL>(a.m + off_a);
+    xa = load_pack<4, NTL>(a.x + off_a);
+    if constexpr (HAS_E) ea = load_pack<4, NTL>(a.e + off_a);
+  }
+  if (sync_b) {
+    gb = load_pack<4, NTL>(a.g + off_b);
+    if constexpr (HAS_M) mb = load_pack<4, NTL>(a.m + off_b);
+    xb = load_pack<4, NTL>(a.x + off_b);
+    if constexpr (HAS_E) {
+      if (reset_b) eb = load_pack<4, NTL>(a.e + off_b);   // e is untouched by the step on a block C_step chose
+    }
+  }
+  if (local_a) {
+    const Pack<4> p = local_update<4, HAS_M>(a.eta, a.beta, ga, ma);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      xa.v[c] = xa.v[c] - p.v[c];
+      if constexpr (HAS_E) ea.v[c] = ea.v[c] - p.v[c];
+    }
+    if constexpr (HAS_M) store_pack<4, NTS>(a.m + off_a, ma);
+    store_pack<4, NTS>(a.x + off_a, xa);
+    if constexpr (HAS_E) store_pack<4, NTS>(a.e + off_a, ea);
+  }
+  if (__any(sync_b)) {   // wavefront-uniform: all 64 lanes take part in the shuffles below
+    Pack<4> p;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) p.v[c] = 0.0f;
+    if (sync_b) {
+      p = local_update<4, HAS_M>(a.eta, a.beta, gb, mb);
+      if constexpr (HAS_M) store_pack<4, NTS>(a.m + off_b, mb);
+    }
+    const float n = static_cast<float>(a.W);
+    if (__any(step_b)) {
+      const Pack<4> psum = worker_sum_in_wave<4>(p, a.W, G, k);
+      if (step_b) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) p.v[c] = psum.v[c] / n;   // p' = pbar, r = 0
+      }
+    }
+    if (sync_b) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        xb.v[c] = xb.v[c] - p.v[c];
+        if constexpr (HAS_E) {
+          if (!step_b) eb.v[c] = eb.v[c] - p.v[c];            // r = p off the blocks C_step chose
+        }
+      }
+    }
+    if (__any(reset_b)) {
+      Pack<4> v;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) v.v[c] = reset_b ? (HAS_E ? eb.v[c] : xb.v[c]) : 0.0f;
+      const Pack<4> vsum = worker_sum_in_wave<4>(v, a.W, G, k);
+      if (reset_b) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float mean = vsum.v[c] / n;
+          if constexpr (HAS_E) {
+            xb.v[c] = (xb.v[c] - eb.v[c]) + mean;
+            eb.v[c] = 0.0f;
+          } else {
+            xb.v[c] = mean;
+          }
+        }
+      }
+    }
+    if (sync_b) {
+      store_pack<4, NTS>(a.x + off_b, xb);
+      if constexpr (HAS_E) {
+        if (reset_b) store_pack<4, NTS>(a.e + off_b, eb);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Error reset (Algorithm 3, t mod H = 0) on the V columns at `col` of a chosen block:
 //   ebar = (e_0 + e_1 + ... + e_{W-1}) / W ;  x_i <- (x_i - e_i) + ebar ;  e_i <- +0
@@ -611,6 +767,17 @@ hipError_t launch_step_range(const StepParams& p, uint64_t col_begin, uint64_t c
   return launch_step_batch<V, false>(p, col_begin, groups, static_cast<uint32_t>(grid), threads, tune.batch, s);
 }
 
+int resolve_nontemporal(const StepParams& p, const Tuning& tune) {
+  int mode = tune.nontemporal;
+  if (mode < 0) {
+    // automatic: a working set that fits the 256 MiB last-level cache is better served by ordinary accesses
+    // (x, e, m come back next iteration; measured +7 % at 110-250 MB), a larger one by non-temporal ones (+10 %)
+    const uint64_t arrays = 2u + (p.e != nullptr ? 1u : 0u) + (p.m != nullptr ? 1u : 0u);
+    mode = static_cast<uint64_t>(p.W) * p.ld * 4u * arrays <= (256ull << 20) ? 0 : 1;
+  }
+  return mode;
+}
+
 template <int C, int NTMODE>
 hipError_t launch_rows_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t grid_size, uint32_t threads,
                              uint32_t order, uint32_t lds, hipStream_t s) {
@@ -634,14 +801,7 @@ hipError_t launch_rows_c(const StepParams& p, uint32_t groups, const Tuning& tun
   if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
   const uint32_t lds = static_cast<uint32_t>(tune.lds_bytes);   // unused by the kernel: only caps workgroups per CU
-  int mode = tune.nontemporal;
-  if (mode < 0) {
-    // automatic: a working set that fits the 256 MiB last-level cache is better served by ordinary accesses
-    // (x, e, m come back next iteration; measured +7 % at 110-250 MB), a larger one by non-temporal ones (+10 %)
-    const uint64_t arrays = 2u + (p.e != nullptr ? 1u : 0u) + (p.m != nullptr ? 1u : 0u);
-    mode = static_cast<uint64_t>(p.W) * p.ld * 4u * arrays <= (256ull << 20) ? 0 : 1;
-  }
-  switch (mode) {
+  switch (resolve_nontemporal(p, tune)) {
     case 0: return launch_rows_flags<C, 0>(p, groups, tiles, grid, threads, order, lds, s);
     case 2: return launch_rows_flags<C, 1>(p, groups, tiles, grid, threads, order, lds, s);
     case 3: return launch_rows_flags<C, 2>(p, groups, tiles, grid, threads, order, lds, s);
@@ -649,7 +809,40 @@ hipError_t launch_rows_c(const StepParams& p, uint32_t groups, const Tuning& tun
   }
 }
 
+template <int NTMODE>
+hipError_t launch_tile_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t grid_size, uint32_t order,
+                             uint32_t log2_w, uint32_t lds, hipStream_t s) {
+  const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
+  const dim3 grid(grid_size), block(64);
+  if (has_e && has_m) hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, true, true>), grid, block, lds, s, p, groups, tiles, order, log2_w);
+  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, true, false>), grid, block, lds, s, p, groups, tiles, order, log2_w);
+  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, false, true>), grid, block, lds, s, p, groups, tiles, order, log2_w);
+  else hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, false, false>), grid, block, lds, s, p, groups, tiles, order, log2_w);
+  return hipGetLastError();
+}
+
+// The balanced kernel: W a power of two <= 64, one-wavefront workgroups, one column group per lane.
+hipError_t launch_tile(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {
+  uint32_t log2_w = 0;
+  while ((1u << log2_w) < p.W) ++log2_w;
+  const uint64_t tiles64 = (static_cast<uint64_t>(groups) + 63) / 64;
+  const uint32_t order = tune.variant == 2 ? 1u : (tune.variant == 3 ? 2u : 0u);
+  uint64_t grid64 = tiles64 * p.W;
+  if (order == 2) grid64 = (grid64 + 7) / 8 * 8;
+  if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+  const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
+  const uint32_t lds = static_cast<uint32_t>(tune.lds_bytes);   // unused by the kernel: only caps workgroups per CU
+  switch (resolve_nontemporal(p, tune)) {
+    case 0: return launch_tile_flags<0>(p, groups, tiles, grid, order, log2_w, lds, s);
+    case 2: return launch_tile_flags<1>(p, groups, tiles, grid, order, log2_w, lds, s);
+    case 3: return launch_tile_flags<2>(p, groups, tiles, grid, order, log2_w, lds, s);
+    default: return launch_tile_flags<3>(p, groups, tiles, grid, order, log2_w, lds, s);
+  }
+}
+
 hipError_t launch_rows(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {
+  const bool w_pow2 = p.W <= 64 && (p.W & (p.W - 1)) == 0;
+  if (tune.balanced && w_pow2 && tune.threads == 64 && tune.cols_per_lane == 1) return launch_tile(p, groups, tune, s);
   switch (tune.cols_per_lane) {
     case 1: return launch_rows_c<1>(p, groups, tune, s);
     case 4: return launch_rows_c<4>(p, groups, tune, s);

@@ -106,8 +106,9 @@ def test_selector_indices_and_masks_are_bit_exact(d, block, R_step, R_reset):
 
 
 # ---------------------------------------------------------------------------- named workloads
-@pytest.mark.parametrize("tuning", [None, {6: 0}, {4: 0}, {4: 0, 6: 0}], ids=["fused-reset", "separate-reset",
-                                                                              "lane-walks-workers", "lane-walks-separate"])
+@pytest.mark.parametrize("tuning", [None, {6: 0}, {8: 0}, {8: 0, 6: 0}, {4: 0}, {4: 0, 6: 0}],
+                         ids=["balanced-fused-reset", "balanced-separate-reset", "worker0-fused-reset",
+                              "worker0-separate-reset", "lane-walks-workers", "lane-walks-separate"])
 def test_tiny_workload_100_steps(tuning):
     wl = I.WORKLOADS["tiny"]
     diff = run_pair(wl, 100, check_every=20, tuning=tuning)
@@ -181,6 +182,7 @@ def test_blocks_chosen_by_both_compressors_at_once():
     for kw in (dict(), dict(W=3), dict(block=6), dict(momentum=0.0)):
         wl = _wl(d=30000, R_step=2, R_reset=2, H=1, **kw)
         assert run_pair(wl, 10) == 0
+        assert run_pair(wl, 10, tuning={8: 0}) == 0
         assert run_pair(wl, 10, tuning={4: 0}) == 0
 
 
@@ -193,7 +195,8 @@ def test_no_momentum_buffer_is_algorithm_2():
 @pytest.mark.parametrize("tuning", [{4: 0}, {4: 0, 0: 1}, {4: 0, 0: 7}, {4: 0, 1: 0}, {4: 0, 2: 1}, {4: 0, 2: 2},
                                     {4: 0, 2: 8}, {4: 0, 0: 3, 1: 0, 2: 8}, {4: 0, 3: 64}, {4: 0, 3: 1024},
                                     {4: 1, 5: 2}, {4: 1, 5: 4, 3: 512}, {4: 2}, {4: 2, 5: 2, 3: 128}, {4: 3},
-                                    {4: 3, 3: 64, 5: 4}, {1: 0}, {1: 2}, {1: 3}, {3: 256}, {3: 1024}, {6: 0}, {6: 0, 4: 0}])
+                                    {4: 3, 3: 64, 5: 4}, {1: 0}, {1: 2}, {1: 3}, {3: 256}, {3: 1024}, {6: 0}, {6: 0, 4: 0}, {8: 0}, {8: 0, 6: 0},
+                                    {8: 0, 1: 0}, {4: 2, 8: 1}, {4: 3, 8: 1, 1: 0}])
 def test_results_do_not_depend_on_launch_shape(tuning):
     wl = _wl(d=30000, W=8, steps=8)
     assert run_pair(wl, 8, tuning=tuning) == 0
@@ -271,7 +274,7 @@ def _random_cases(n, seed):
             lr=float(rng.choice([0.1, 0.01, 1.0])), seed=int(rng.integers(0, 2**62)),
             ld=int(rng.choice([d, -(-d // 4) * 4, -(-d // 64) * 64, -(-d // 1024) * 1024])),
             with_error=bool(rng.integers(0, 2)), with_momentum=bool(momentum != 0.0 or rng.integers(0, 2)),
-            tuning=[None, {4: 0}, {4: 2, 5: 2}, {6: 0}, {3: 256, 5: 4}, {4: 3, 1: 0}][int(rng.integers(0, 6))]))
+            tuning=[None, {4: 0}, {4: 2, 5: 2}, {6: 0}, {3: 256, 5: 4}, {4: 3, 1: 0}, {8: 0}, None][int(rng.integers(0, 8))]))
     return cases
 
 
