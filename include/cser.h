@@ -156,7 +156,8 @@ int cser_profile_clear(cser_ctx* ctx);
  *   key 5  row-split variants: 4-column groups per lane, 1 (default), 2 or 4
  *   key 6  1 (default) = on iterations with t mod H = 0 the error reset runs inside the fused-step kernel
  *          (x and e of the reset blocks make one trip instead of two); 0 = separate reset kernel
- *   key 7  bytes of (unused) dynamic LDS per workgroup, 0 .. 65536 (default 10240): caps workgroups per CU
+ *   key 7  bytes of (unused) dynamic LDS per workgroup, 0 .. 65536: caps workgroups per CU; -1 (default) = 8192,
+ *          7168 or 0 for 4, 3 or 2 load streams per wavefront
  *   key 8  1 (default) = for W a power of two <= 64 the blocks that need the worker mean are shared out over the W
  *          workgroups of a tile (in-wavefront ordered sums); 0 = worker 0's workgroup walks all rows for them
  *   key 0  variant 0: workgroup cap (0 = one group per lane; n > 0 = at most n workgroups, lanes loop)

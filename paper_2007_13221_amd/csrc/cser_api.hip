@@ -415,7 +415,7 @@ int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
       ctx->tuning.balanced = value != 0;
       return CSER_OK;
     case 7:
-      if (value < 0 || value > 65536) return CSER_EINVAL;
+      if (value < -1 || value > 65536) return CSER_EINVAL;
       ctx->tuning.lds_bytes = static_cast<int>(value);
       return CSER_OK;
     case 6:

@@ -42,8 +42,7 @@ struct Tuning {
   int batch = 4;        // workers whose loads are issued together
   int threads = 64;     // workgroup size of the fused-step kernel (one wavefront: measured best)
   int variant = 1;      // 0: a lane walks all workers; row-split: 1 tiles fastest, 2 workers fastest, 3 per-XCD sweeps
-  int lds_bytes = 10240;  // dynamic LDS requested per workgroup and never touched: caps a CU at 16 one-wavefront
-                          // workgroups (4 per SIMD); measured 4-5 % faster than uncapped (up to 32), plateau 14..20
+  int lds_bytes = -1;   // dynamic LDS requested per workgroup and never touched (occupancy cap); -1: by stream count
   int balanced = 1;     // W a power of two <= 64: every workgroup of a tile takes 1/W of its synchronised work
   int fuse_reset = 1;   // on reset iterations do the error reset inside the fused-step kernel
   int cols_per_lane = 1;  // row-split variants: 4-column groups per lane

@@ -767,6 +767,17 @@ hipError_t launch_step_range(const StepParams& p, uint64_t col_begin, uint64_t c
   return launch_step_batch<V, false>(p, col_begin, groups, static_cast<uint32_t>(grid), threads, tune.batch, s);
 }
 
+// Occupancy cap of the row-split kernels: bytes of dynamic LDS requested per one-wavefront workgroup and
+// never touched.  What the memory system likes is a bounded number of requests in flight per CU, so the
+// cap follows the number of load streams per wavefront: 4 streams (g, m, x, e) -> 8 KiB = 20 wavefronts
+// per CU, 3 streams -> 7 KiB = 22, 2 streams (x only) -> no cap (measured: each is the best or within
+// 0.5 % of the best of a sweep, and 4-19 % better than the wrong one).
+uint32_t resolve_lds(const StepParams& p, const Tuning& tune) {
+  if (tune.lds_bytes >= 0) return static_cast<uint32_t>(tune.lds_bytes);
+  const int streams = 2 + (p.e != nullptr ? 1 : 0) + (p.m != nullptr ? 1 : 0);
+  return streams >= 4 ? 8192u : (streams == 3 ? 7168u : 0u);
+}
+
 int resolve_nontemporal(const StepParams& p, const Tuning& tune) {
   int mode = tune.nontemporal;
   if (mode < 0) {
@@ -800,7 +811,7 @@ hipError_t launch_rows_c(const StepParams& p, uint32_t groups, const Tuning& tun
   if (order == 2) grid64 = (grid64 + 7) / 8 * 8;
   if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
-  const uint32_t lds = static_cast<uint32_t>(tune.lds_bytes);   // unused by the kernel: only caps workgroups per CU
+  const uint32_t lds = resolve_lds(p, tune);
   switch (resolve_nontemporal(p, tune)) {
     case 0: return launch_rows_flags<C, 0>(p, groups, tiles, grid, threads, order, lds, s);
     case 2: return launch_rows_flags<C, 1>(p, groups, tiles, grid, threads, order, lds, s);
@@ -831,7 +842,7 @@ hipError_t launch_tile(const StepParams& p, uint32_t groups, const Tuning& tune,
   if (order == 2) grid64 = (grid64 + 7) / 8 * 8;
   if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
   const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
-  const uint32_t lds = static_cast<uint32_t>(tune.lds_bytes);   // unused by the kernel: only caps workgroups per CU
+  const uint32_t lds = resolve_lds(p, tune);
   switch (resolve_nontemporal(p, tune)) {
     case 0: return launch_tile_flags<0>(p, groups, tiles, grid, order, log2_w, lds, s);
     case 2: return launch_tile_flags<1>(p, groups, tiles, grid, order, log2_w, lds, s);
