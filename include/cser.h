@@ -26,7 +26,8 @@
  *   - kernels are enqueued on the hipStream_t passed as `void* hip_stream` (NULL = the null
  *     stream) and the call returns without waiting for them;
  *   - a context is bound to the device that was current at cser_create() and must be used with
- *     that device current; calls on one context must not overlap each other.
+ *     that device current (cser_step and cser_error_reset return CSER_EINVAL otherwise); calls on one context
+ *     must not overlap each other.
  */
 #ifndef CSER_H
 #define CSER_H

@@ -39,10 +39,17 @@ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// A context's buffers and small arrays live on one device: calls must be made with it current.
+bool on_its_device(int device) {
+  int current = -1;
+  return device < 0 || (hipGetDevice(&current) == hipSuccess && current == device);
+}
+
 }  // namespace
 
 struct cser_ctx {
   cser_config cfg;
+  int device;                // the device that was current at cser_create
   float* x;
   float* e;
   float* m;
@@ -80,7 +87,7 @@ int record_begin(cser_ctx* ctx, int which, hipStream_t s, bool* timed) {
     CSER_HIP(hipEventCreate(&a));
     hipError_t err = hipEventCreate(&b);
     if (err != hipSuccess) {
-      hipEventDestroy(a);
+      (void)hipEventDestroy(a);
       return hip_failed(err, "hipEventCreate");
     }
     tm.begin.push_back(a);
@@ -152,6 +159,7 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
   cser_ctx* ctx = new (std::nothrow) cser_ctx();
   if (!ctx) return CSER_ENOMEM;
   ctx->cfg = *cfg;
+  if (hipGetDevice(&ctx->device) != hipSuccess) ctx->device = -1;
   ctx->x = x;
   ctx->e = e;
   ctx->m = m;
@@ -204,7 +212,7 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
 }
 
 int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
-  if (!ctx) return CSER_EINVAL;
+  if (!ctx || !on_its_device(ctx->device)) return CSER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (ctx->k_reset == 0) return CSER_OK;
   CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, 0u, 1u, static_cast<uint32_t>(ctx->B), ctx->k_reset,
@@ -226,7 +234,7 @@ int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
 }
 
 int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
-  if (!ctx || !g) return CSER_EINVAL;
+  if (!ctx || !g || !on_its_device(ctx->device)) return CSER_EINVAL;
   if (!aligned(g, 4)) return CSER_EALIGN;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint64_t t = ctx->t + 1;
