@@ -72,8 +72,9 @@ typedef struct cser_config {
  *      momentum = 0 (Algorithm 2 keeps no momentum) and removes the m traffic.
  * The buffers stay owned by the caller, must outlive the context and are never freed here.  The
  * context owns a few small device arrays (block masks and index lists).  The zero fills are
- * enqueued on hip_stream.  Vectorised kernels are used when ld and block are multiples of 4 and
- * the pointers are 16-byte aligned; any other layout runs element-wise kernels with the same
+ * enqueued on hip_stream.  128-bit accesses are used whenever block is a multiple of 4 columns, whatever
+ * ld and the base addresses are (rows that start on 16-byte boundaries, i.e. ld % 4 == 0 and aligned
+ * bases, are faster, and ld a multiple of 1024 is fastest); other block sizes run element-wise kernels with the same
  * results.  On failure *out is NULL.
  */
 int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_stream, cser_ctx** out);

@@ -56,7 +56,7 @@ struct cser_ctx {
   uint64_t B;
   uint32_t k_step, k_reset;
   uint64_t t;
-  bool vector_layout;        // ld, block multiples of 4 and x, e, m 16-byte aligned
+  bool vector_layout;        // block is a multiple of 4 columns: a 4-column group never straddles two blocks
   uint8_t* mask_step;        // device, window * B bytes: C_step's masks for iterations win_t0 .. win_t0 + win_n - 1
   uint32_t window;           // iterations drawn per selector launch
   uint64_t win_t0;
@@ -167,7 +167,7 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
   ctx->k_step = cfg->R_step == 0 ? 0u : static_cast<uint32_t>(ceil_div(ctx->B, cfg->R_step));
   ctx->k_reset = static_cast<uint32_t>(ceil_div(ctx->B, cfg->R_reset));
   ctx->t = 0;
-  ctx->vector_layout = cfg->ld % 4 == 0 && cfg->block % 4 == 0 && aligned(x, 16) && aligned(e, 16) && aligned(m, 16);
+  ctx->vector_layout = cfg->block % 4 == 0;
   if (!ctx->vector_layout && cfg->d > 0xFFFFFFFFull) {
     delete ctx;
     return CSER_ERANGE;   // the element-wise kernels index columns with 32 bits
@@ -284,7 +284,7 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
   bool timed = false;
   int rc = record_begin(ctx, 0, s, &timed);
   if (rc != CSER_OK) return rc;
-  CSER_HIP(cser::launch_step(p, ctx->vector_layout && aligned(g, 16), ctx->tuning, s));
+  CSER_HIP(cser::launch_step(p, ctx->vector_layout, ctx->tuning, s));
   rc = record_end(ctx, 0, s, timed);
   if (rc != CSER_OK) return rc;
   ctx->t = t;

@@ -53,8 +53,8 @@ struct Tuning {
 hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint64_t t_stride, uint32_t count, uint32_t B,
                            uint32_t k, uint8_t* mask, uint32_t* idx, hipStream_t s);
 
-// Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d).  `vectorised` requires ld and
-// block multiples of 4 and 16-byte aligned rows.
+// Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d).  `vectorised` requires block to be a
+// multiple of 4 columns (rows need only 4-byte alignment).
 hipError_t launch_step(const StepParams& p, bool vectorised, const Tuning& tune, hipStream_t s);
 
 // Error reset on the chosen blocks (idx: the k chosen ids; mask: the same choice as B bytes).

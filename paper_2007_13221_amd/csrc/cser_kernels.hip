@@ -33,9 +33,13 @@ namespace cser {
 namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+// The same 128-bit vector, promised to be only 4-byte aligned: gfx950 takes global_load/store_dwordx4 at any
+// dword address, so rows whose start is not a multiple of 16 bytes (ld % 4 != 0, odd base addresses) still
+// move 128 bits per lane; on 16-byte aligned rows the instruction is the same and nothing is lost.
+typedef f4 f4_dword_aligned __attribute__((aligned(4)));
 
 // ------------------------------------------------------------------------------------------
-// V consecutive fp32 values (V = 4: one 128-bit access; V = 1: the unaligned fallback).
+// V consecutive fp32 values (V = 4: one 128-bit access; V = 1: blocks that are not a multiple of 4 columns).
 // ------------------------------------------------------------------------------------------
 template <int V>
 struct Pack {
@@ -47,8 +51,8 @@ __device__ __forceinline__ Pack<V> load_pack(const float* p) {
   Pack<V> r;
   if constexpr (V == 4) {
     f4 t;
-    if constexpr (NT) t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
-    else t = *reinterpret_cast<const f4*>(p);
+    if constexpr (NT) t = __builtin_nontemporal_load(reinterpret_cast<const f4_dword_aligned*>(p));
+    else t = *reinterpret_cast<const f4_dword_aligned*>(p);
     r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
   } else {
     if constexpr (NT) r.v[0] = __builtin_nontemporal_load(p);
@@ -62,8 +66,8 @@ __device__ __forceinline__ void store_pack(float* p, const Pack<V>& r) {
   if constexpr (V == 4) {
     f4 t;
     t.x = r.v[0]; t.y = r.v[1]; t.z = r.v[2]; t.w = r.v[3];
-    if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<f4*>(p));
-    else *reinterpret_cast<f4*>(p) = t;
+    if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<f4_dword_aligned*>(p));
+    else *reinterpret_cast<f4_dword_aligned*>(p) = t;
   } else {
     if constexpr (NT) __builtin_nontemporal_store(r.v[0], p);
     else *p = r.v[0];

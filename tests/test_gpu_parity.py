@@ -145,7 +145,7 @@ def _wl(**kw):
     dict(d=1, block=1, W=2),
     dict(d=4099, block=4),                    # smallest vector block, ragged d
     dict(d=4099, block=1),                    # element-wise blocks
-    dict(d=4099, block=6),                    # block not a multiple of 4: element-wise kernels
+    dict(d=4099, block=6),                    # block not a multiple of 4: the only case for element-wise kernels
     dict(d=70000, block=4096, R_step=2),      # block larger than a workgroup's columns
     dict(momentum=0.0),
     dict(lr=0.0),
@@ -159,7 +159,7 @@ def test_edge_cases_match_bit_for_bit(kw):
     assert run_pair(wl, wl.steps) == 0
 
 
-def test_row_stride_equal_to_unaligned_d_uses_elementwise_kernels():
+def test_row_stride_equal_to_an_odd_d_keeps_rows_only_4_byte_aligned():
     wl = _wl(d=4099)
     assert run_pair(wl, 12, ld=4099) == 0
 
