@@ -325,3 +325,22 @@ def test_step_size_can_change_between_iterations():
         m = 0.9 * m + g
         xbar -= (lr * (0.9 * m + g)).mean(axis=0)
     np.testing.assert_allclose(o.x.mean(axis=0), xbar, rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------- the worked numbers of Section 4.2
+def test_compression_error_term_reproduces_the_numbers_printed_in_section_4_2():
+    """Theorem 1's compression-error factor [4(1-d1)/d1^2 + 1](1-d2) H^2 (constants dropped, as the text does)
+    against the four numbers the paper prints; the same (d1, d2, H) reading drives test_residual_after_reset_obeys_lemma3_bound."""
+    def cser_term(d1, d2, H):
+        return (Fraction(4) * (1 - d1) / d1 ** 2 + 1) * (1 - d2) * H ** 2
+
+    def qsparse_term(d1, H):
+        return (Fraction(4) * (1 - d1 ** 2) / d1 ** 2 + 1) * H ** 2
+
+    half = Fraction(1, 2)
+    assert qsparse_term(half, 8) == 832 and cser_term(half, 0, 8) == 576          # Remark 1's example
+    assert cser_term(Fraction(1, 3), 0, 4) == 400                                   # all budget on the reset
+    moved = cser_term(Fraction(7, 8), Fraction(1, 96), 12)                          # some budget moved to the step
+    assert 235 < moved < 236
+    # "the overall compression budget remains the same": delta_1 / H + delta_2 is 1/12 in both settings
+    assert Fraction(1, 3) / 4 == Fraction(7, 8) / 12 + Fraction(1, 96)
