@@ -139,6 +139,44 @@ def test_full_error_reset_makes_local_models_coincide():
     np.testing.assert_allclose(o.x[0], z, rtol=0, atol=1e-13)
 
 
+# ---------------------------------------------------------------- error reset, block by block, in float32
+def test_error_reset_touches_only_the_blocks_it_chose_and_follows_the_written_formula_there():
+    """Algorithm 3's reset branch in float32 on non-dyadic values, where (x - e) + e != x in general.
+
+    Off the blocks C_reset chose, Algorithm PSync gives C(e_i) = 0 on every worker, hence e'_i = 0 + r_i = e_i
+    exactly and the correction -e_i + e'_i of the model is identically zero: x and e must come out
+    bit-identical (implementation II of Appendix A.4, which the paper states to be equivalent, does not visit
+    those blocks either).  On the chosen blocks r_i = 0, e'_i = ebar, so x_i <- (x_i - e_i) + ebar with ebar
+    the left-to-right float32 sum over the workers divided by n, and e_i <- +0."""
+    rng = np.random.default_rng(31)
+    W, d, block, seed, T = 5, 203, 8, 19, 7           # ragged last block of 3 columns, n not a power of two
+    B = -(-d // block)
+    x0 = (rng.standard_normal(d) / 3.0).astype(np.float32)
+    o = R.OracleCSER(d, W, block, 4, 3, 0, 0.1, 0.9, seed, x0, dtype=np.float32)    # H = 0: no automatic reset
+    for g in _grads(rng, T, W, d, 0.1):
+        o.step(g.astype(np.float32))
+    x_before, e_before = o.x.copy(), o.e.copy()
+    o.error_reset()
+    cols = M.column_mask(R.select_blocks(seed, 1, T, B, R.blocks_kept(B, 3))[1], d, block)
+    assert 0 < cols.sum() < d
+    # unchosen blocks: nothing moves, not even by a rounding
+    assert np.array_equal(o.x[:, ~cols].view(np.uint32), x_before[:, ~cols].view(np.uint32))
+    assert np.array_equal(o.e[:, ~cols].view(np.uint32), e_before[:, ~cols].view(np.uint32))
+    # the literal (x - e) + e would have moved some of them: the test separates the two readings
+    literal = (x_before - e_before) + e_before
+    assert (literal[:, ~cols] != x_before[:, ~cols]).any()
+    # chosen blocks: the written formula, float32 operation by operation
+    ebar = e_before[0].copy()
+    for i in range(1, W):
+        ebar = ebar + e_before[i]
+    ebar = ebar / np.float32(W)
+    want = (x_before - e_before) + ebar[None, :]
+    assert want.dtype == np.float32
+    assert np.array_equal(o.x[:, cols].view(np.uint32), want[:, cols].view(np.uint32))
+    assert not o.e[:, cols].any() and not np.signbit(o.e[:, cols]).any()
+    assert np.abs(e_before[:, cols]).max() > 1e-3     # there was a residual to reset
+
+
 # ---------------------------------------------------------------- one worker = plain SGD
 @pytest.mark.parametrize("R_step,R_reset,H", [(4, 2, 3), (0, 1, 1), (1, 5, 2), (7, 7, 0)])
 def test_single_worker_is_plain_momentum_sgd(R_step, R_reset, H):

@@ -27,6 +27,7 @@ MUTANTS = [
     ("residual accumulated with wrong sign", "e[i * pb.ld + j] = e[i * pb.ld + j] - r[i * n + j]", "e[i * pb.ld + j] = e[i * pb.ld + j] + r[i * n + j]"),
     ("reset forgets to remove the old residual", "(x[i * pb.ld + j] - ehalf[i * n + j]) + eprime[i * n + j]", "x[i * pb.ld + j] + eprime[i * n + j]"),
     ("reset corrects the model on the unchosen blocks only", "if (chosen[(pb.col0 + j) / pb.block])\n        x[", "if (!chosen[(pb.col0 + j) / pb.block])\n        x["),
+    ("reset sends the unchosen blocks through (x - e) + e' too", "if (chosen[(pb.col0 + j) / pb.block])\n        x[", "if (true)\n        x["),
     ("reset keeps the old residual", "e[i * pb.ld + j] = r[i * n + j];", "e[i * pb.ld + j] = ehalf[i * n + j];"),
     ("reset reuses the step's blocks", "select_blocks(pb.seed, 1, t, B, blocks_kept(B, R_reset), nullptr, chosen.data());\n  std::vector<real> ehalf", "select_blocks(pb.seed, 0, t, B, blocks_kept(B, R_reset), nullptr, chosen.data());\n  std::vector<real> ehalf"),
     ("compressor keeps the complement", "cv[j] = chosen[b] ? v[j] : real(0)", "cv[j] = chosen[b] ? real(0) : v[j]"),
@@ -45,6 +46,7 @@ def _suite():
     TM.test_non_power_of_two_worker_count_against_exact_arithmetic()
     TM.test_a_block_slice_evolves_exactly_as_in_the_full_run()
     TM.test_implementations_one_and_two_give_the_same_models(4, 2, 3, 0.9)
+    TM.test_error_reset_touches_only_the_blocks_it_chose_and_follows_the_written_formula_there()
     TS.test_permutation_is_bijection_and_inverse_matches(17)
     TS.test_permutation_is_bijection_and_inverse_matches(257)
     TS.test_exactly_k_distinct_blocks_and_mask_agrees(7, 100)
