@@ -1,14 +1,17 @@
 """Benchmark of the CSER update on one MI355X.
 
-A "step" is one call of cser_step: block selection, the fused local step + partial synchronisation
-+ residual bookkeeping, and the error reset on the iterations where t mod H = 0 -- the whole hot
-path.  The workload is the large-CNN-sized configuration the headline metric is quoted on
+A "step" is one iteration of Algorithm 3 through the C ABI: block selection, the fused local step + partial
+synchronisation + residual bookkeeping, and the error reset on the iterations where t mod H = 0 -- the whole
+hot path.  The workload is the large-CNN-sized configuration the headline metric is quoted on
 (d = 25,557,032, W = 8, block 1024, R_step 256, R_reset 16, H 32); states and two rotating gradient
 buffers are resident in HBM before the timed region, gradients are synthetic N(0, 1e-3).
 
 Prints one JSON line: whole-job param-elements/s, the HBM roofline of the fused-step kernel
 (algorithmic bytes per launch / HIP-event duration per launch, measured in the same timed region),
 and the CPU oracle timed on a bounded sample of the same workload.
+
+The timed iterations always contain at least one redraw of the block-mask window and, when H > 0, at least
+one error reset: with few steps the iteration counter is moved (cser_set_step) so that they do.
 """
 import argparse
 import json
@@ -22,6 +25,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
+TUNING_KEYS = {"kernel": 0, "nontemporal": 1, "fuse_reset": 2, "tile_waves_per_cu": 3, "shared_groups_per_cu": 4}
+KERNEL_NAMES = {"launches_tile": "cser_step_tile_kernel", "launches_shared": "cser_step_shared_kernel",
+                "launches_general": "cser_step_general_kernel"}
 
 
 def step_bytes(wl, d_sel, with_error=True, with_momentum=True):
@@ -30,6 +36,11 @@ def step_bytes(wl, d_sel, with_error=True, with_momentum=True):
     per = 4 * (1 + (2 if with_momentum else 0) + 2 + (2 if with_error else 0))
     sel = per - (8 if with_error else 0)
     return wl.W * (per * (wl.d - d_sel) + sel * d_sel)
+
+
+def reset_bytes(wl, d_sel, with_error=True):
+    """Algorithmic bytes of one error reset: read e, x and write x, e on the chosen columns (implementation II: x only)."""
+    return (16 if with_error else 8) * wl.W * d_sel
 
 
 def chosen_columns(wl, mask):
@@ -41,19 +52,22 @@ def chosen_columns(wl, mask):
 
 
 def read_traffic(workload):
-    """HBM bytes per fused-step launch from the committed counter summary, or None."""
-    path = os.path.join(ROOT, "profiles", f"fused_step_{workload}_hbm_traffic.txt")
+    """HBM bytes per fused-step launch from the committed counter summary (a constant of an earlier counter run
+    of this same command, not a counter of this run), or (None, None)."""
+    rel = os.path.join("profiles", f"fused_step_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
-    return float(m.group(1)) if m else None
+    return (float(m.group(1)), rel) if m else (None, None)
 
 
 def cpu_baseline(wl, variant_e=True, variant_m=True):
     """The oracle as it stands, one host thread, on a slice of the workload's blocks."""
     import numpy as np
     from oracle import reference as R
-    steps = wl.H                                   # one full reset period, so the reset is included
+    steps = max(wl.H, 1)                           # one full reset period, so the reset is included
+    steps = min(steps, 32)
     nb = max(1, wl.B // 4)
     ncols = min(wl.d, nb * wl.block)
     rng = np.random.default_rng(wl.seed)
@@ -67,12 +81,27 @@ def cpu_baseline(wl, variant_e=True, variant_m=True):
     dt = time.perf_counter() - t0
     return {"value": ncols * steps / dt, "unit": "param-elements/s", "cores": 1, "kind": "oracle",
             "sample": f"blocks [0, {nb}) of {wl.B} ({ncols} of {wl.d} columns, all {wl.W} workers), {steps} steps "
-                      f"incl. one error reset, block choice over all blocks; {dt:.1f} s on one host thread",
+                      f"incl. {steps // wl.H if wl.H else 0} error reset(s), block choice over all blocks; {dt:.1f} s on one host thread",
             "host_cpus": os.cpu_count()}
 
 
-def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, variant_m=True):
-    """Time `steps` calls of cser_step on one workload; returns the fields of the JSON line."""
+def place_timed_region(B, ctx, wl, steps):
+    """Move the iteration counter, if need be, so that the next `steps` iterations hold a redraw of the mask
+    window and (H > 0) an error reset.  Returns the first timed iteration."""
+    t_now = B.cser_get_step(ctx)
+    first, last = t_now + 1, t_now + steps
+    has_reset = wl.H > 0 and (last // wl.H) * wl.H >= first
+    if steps >= 64 and (has_reset or wl.H == 0):
+        return first                                  # long enough to hold both anyway (the window is 32 iterations)
+    back = (3 * steps) // 4                           # the reset falls three quarters into the region
+    period = wl.H if wl.H > 0 else 32
+    r = -(-(t_now + 33 + back) // period) * period    # beyond the window drawn so far: the first timed step redraws
+    B.cser_set_step(ctx, r - back - 1)
+    return r - back
+
+
+def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, variant_m=True, second_pass=True):
+    """Time `steps` iterations on one workload; returns the fields of the JSON line."""
     import torch
     from paper_2007_13221_amd import binding as B
     from paper_2007_13221_amd import inputs as I
@@ -83,41 +112,58 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
     opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=variant_e, with_momentum=variant_m)
     for item in tune:
         key, value = item.split("=")
-        B.cser_set_tuning(opt.ctx, int(key), int(value))
+        B.cser_set_tuning(opt.ctx, TUNING_KEYS.get(key, key if not key.isdigit() else int(key)), int(value))
     grads = [I.gradient(wl, t, dev) for t in (1, 2)]   # generated outside every timed region
+    stream = torch.cuda.current_stream().cuda_stream
+    glist = B.gradient_list([grads[t & 1] for t in range(steps)])
     torch.cuda.synchronize()
 
     for t in range(warmup):
         opt.step(grads[t & 1])
     torch.cuda.synchronize()
 
+    # ---- the timed region: `steps` iterations, every fused-step and reset launch bracketed by HIP events
+    t_first = place_timed_region(B, opt.ctx, wl, steps)
+    before = B.cser_measure_counters(opt.ctx)
     B.cser_profile_enable(opt.ctx, True)
     B.cser_profile_clear(opt.ctx)
-    t_first = B.cser_get_step(opt.ctx) + 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for t in range(steps):
-        opt.step(grads[t & 1])
+    B.cser_step_many(opt.ctx, glist, stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     step_ms, step_launches = B.cser_profile_read(opt.ctx, 0)
     reset_ms, reset_launches = B.cser_profile_read(opt.ctx, 1)
     B.cser_profile_enable(opt.ctx, False)
+    after = B.cser_measure_counters(opt.ctx)
+    delta = {k: after[k] - before[k] for k in after}
 
-    # algorithmic bytes of the timed launches (block lists recomputed by the GPU selector afterwards).  A reset that
-    # ran inside the fused-step kernel adds no bytes here: its blocks' x and e are already counted once by the step.
-    resets_fused = reset_launches == 0
+    # ---- the same iterations once more without the events (they cost host and GPU time that matters at small d)
+    plain = None
+    if second_pass:
+        B.cser_set_step(opt.ctx, t_first - 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.cser_step_many(opt.ctx, glist, stream)
+        torch.cuda.synchronize()
+        plain = time.perf_counter() - t0
+
+    # algorithmic bytes of the timed launches (block lists recomputed by the GPU selector afterwards)
     total_step_bytes = 0
     total_reset_bytes = 0
-    resets = 0
+    synced_columns = 0
     for t in range(t_first, t_first + steps):
         _, mask = B.cser_select_blocks(opt.ctx, 0, t)
-        total_step_bytes += step_bytes(wl, chosen_columns(wl, mask), variant_e, variant_m)
+        cols = chosen_columns(wl, mask)
+        synced_columns += cols
+        total_step_bytes += step_bytes(wl, cols, variant_e, variant_m)
         if wl.H and t % wl.H == 0:
-            resets += 1
-            if not resets_fused:
-                _, rmask = B.cser_select_blocks(opt.ctx, 1, t)
-                total_reset_bytes += (16 if variant_e else 8) * wl.W * chosen_columns(wl, rmask)
+            _, rmask = B.cser_select_blocks(opt.ctx, 1, t)
+            rcols = chosen_columns(wl, rmask)
+            synced_columns += rcols
+            total_reset_bytes += reset_bytes(wl, rcols, variant_e)
+    # The fused-step kernel is credited with the step's bytes only, also on iterations where it carries the error
+    # reset out as well (x and e of those blocks are in registers already): its figure is never overstated.
     bytes_per_launch = total_step_bytes / steps
     kernel_ms = step_ms / max(step_launches, 1)
     achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
@@ -140,6 +186,9 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
         del dst
 
     kind = ("implementation I" if variant_e else "implementation II (no e)") + ("" if variant_m else ", no momentum buffer")
+    kernels = {KERNEL_NAMES[k]: delta[k] for k in KERNEL_NAMES if delta[k]}
+    traffic, traffic_source = read_traffic(wl.name) if (variant_e and variant_m and not tune) else (None, None)
+    whole_bytes = total_step_bytes + total_reset_bytes
     out = {
         "metric": "CSER step param-elements/s and achieved HBM GB/s (% of peak) at d=25.6M, W=8",
         "value": wl.d * steps / elapsed,
@@ -153,21 +202,44 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
                                f"g~N(0,{wl.g_var}), seed={wl.seed}; steps t={t_first}..{t_first + steps - 1}; {kind}",
                    "resident": "x, e, m [W][ld] fp32 + 2 rotating g buffers", "ld": wl.ld},
         "worker_elements_per_s": wl.W * wl.d * steps / elapsed,
-        "whole_path_GBps": (total_step_bytes + total_reset_bytes) / elapsed / 1e9,
-        "whole_path_frac_of_peak": (total_step_bytes + total_reset_bytes) / elapsed / 1e9 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "cser_step_tile_kernel" if (wl.W & (wl.W - 1)) == 0 and wl.W <= 64 and not tune else "cser_step_*_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": read_traffic(wl.name) if (variant_e and variant_m) else None,
-                     "bytes_per_launch": bytes_per_launch, "ms_per_launch": kernel_ms, "launches": step_launches},
-        "resets": {"in_timed_region": resets, "fused_into_step_kernel": resets_fused,
+        "whole_path_GBps": whole_bytes / elapsed / 1e9,
+        "whole_path_frac_of_peak": whole_bytes / elapsed / 1e9 / HBM_PEAK_GBPS,
+        "whole_path_bytes": "algorithmic: fused step 4*W*(7d - 2 d_sel) per iteration plus 16*W*d_sel' per error reset",
+        "roofline": {"bound": "hbm", "kernel": max(kernels, key=kernels.get) if kernels else None, "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "bytes_per_launch": bytes_per_launch, "ms_per_launch": kernel_ms, "launches": step_launches,
+                     "launches_by_kernel": kernels},
+        "selector": {"window_draws_in_timed_region": delta["window_draws"]},
+        "resets": {"in_timed_region": delta["resets_fused"] + delta["resets_separate"],
+                   "fused_into_step_kernel": delta["resets_fused"],
                    "separate_kernel_launches": reset_launches,
                    "separate_kernel_ms_per_launch": reset_ms / max(reset_launches, 1)},
+        "overall_compression_ratio": {"counted": wl.d * steps / synced_columns if synced_columns else None,
+                                      "section_5_1_formula": B.cser_overall_ratio(cfg)},
+        "without_kernel_events": None if plain is None else {"ms_per_step": plain * 1e3 / steps,
+                                                             "value": wl.d * steps / plain},
         "copy_kernel_GBps": copy_gbps,
     }
     opt.close()
     del opt, grads
     torch.cuda.empty_cache()
     return out
+
+
+def compact(wl, r):
+    return {"workload": wl.name, "R_step": wl.R_step, "R_reset": wl.R_reset, "block": wl.block, "H": wl.H,
+            "steps": r["steps"], "ms_per_step": round(r["ms_per_step"], 4),
+            "G_param_elements_per_s": round(r["value"] / 1e9, 2),
+            "step_kernel_ms": round(r["roofline"]["ms_per_launch"], 4),
+            "step_kernel_GBps": round(r["roofline"]["achieved"], 1),
+            "step_kernel_frac_of_peak": round(r["roofline"]["frac"], 3),
+            "kernels": r["roofline"]["launches_by_kernel"],
+            "whole_path_GBps": round(r["whole_path_GBps"], 1),
+            "whole_path_frac_of_peak": round(r["whole_path_frac_of_peak"], 3),
+            "resets": r["resets"]["in_timed_region"],
+            "overall_ratio_counted": round(r["overall_compression_ratio"]["counted"], 2) if r["overall_compression_ratio"]["counted"] else None,
+            "overall_ratio_formula": round(r["overall_compression_ratio"]["section_5_1_formula"], 2)}
 
 
 def main():
@@ -182,8 +254,11 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the one headline line: one compact line per point of the 40-point compression "
                          "sweep at the large-CNN size (50 steps each)")
+    ap.add_argument("--table4", action="store_true",
+                    help="one compact line per CSER row of the paper's Table 4 (compressor pair and reset interval for "
+                         "each overall ratio) at the large-CNN size, max(64, 2 H) steps each")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
-                    help="cser_set_tuning(key, value) before the run (launch-shape experiments)")
+                    help="cser_set_tuning(key, value) before the run (launch-shape experiments); keys: " + ", ".join(TUNING_KEYS))
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all W worker states are resident on it and the worker "
@@ -196,19 +271,16 @@ def main():
         sys.exit("bench.py: no GPU visible")
     variant_e = not args.variant.startswith("II")
     variant_m = not args.variant.endswith("nomomentum")
-    if args.sweep:
-        for wl in I.sweep_workloads():
-            r = run_workload(wl, wl.steps, 5, args.tune, with_copy=False, variant_e=variant_e, variant_m=variant_m)
-            print(json.dumps({"workload": wl.name, "R_step": wl.R_step, "block": wl.block, "H": wl.H,
-                              "steps": wl.steps, "ms_per_step": round(r["ms_per_step"], 4),
-                              "G_param_elements_per_s": round(r["value"] / 1e9, 2),
-                              "step_kernel_ms": round(r["roofline"]["ms_per_launch"], 4),
-                              "step_kernel_GBps": round(r["roofline"]["achieved"], 1),
-                              "step_kernel_frac_of_peak": round(r["roofline"]["frac"], 3),
-                              "whole_path_GBps": round(r["whole_path_GBps"], 1)}), flush=True)
+    if args.sweep or args.table4:
+        points = I.sweep_workloads() if args.sweep else I.table4_workloads()
+        for wl in points:
+            r = run_workload(wl, wl.steps, 5, args.tune, with_copy=False, variant_e=variant_e, variant_m=variant_m,
+                             second_pass=False)
+            print(json.dumps(compact(wl, r)), flush=True)
         return
     named = dict(I.WORKLOADS)
     named.update({w.name: w for w in I.sweep_workloads()})
+    named.update({w.name: w for w in I.table4_workloads()})
     wl = named[args.workload]
     out = run_workload(wl, args.steps, args.warmup, args.tune, variant_e=variant_e, variant_m=variant_m)
     if not args.no_cpu_baseline:

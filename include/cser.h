@@ -44,7 +44,7 @@ typedef enum cser_status {
   CSER_EALIGN = -2,  /* a device pointer is not 4-byte aligned                                            */
   CSER_ENOMEM = -3,  /* host or device allocation failed                                                  */
   CSER_EHIP = -4,    /* a HIP runtime call failed; cser_last_hip_error() names it                          */
-  CSER_ERANGE = -5   /* a size is beyond what the kernels index (B >= 2^32 or d/4 >= 2^32)                 */
+  CSER_ERANGE = -5   /* a size is beyond what the kernels index (B >= 2^32, d/4 >= 2^32, W * ceil(d/256) >= 2^31) */
 } cser_status;
 
 typedef struct cser_ctx cser_ctx; /* opaque, host-side */
@@ -71,8 +71,10 @@ typedef struct cser_config {
  *   m  device [W][ld] fp32 or NULL.  Non-NULL: zero-filled here.  NULL is allowed only with
  *      momentum = 0 (Algorithm 2 keeps no momentum) and removes the m traffic.
  * The buffers stay owned by the caller, must outlive the context and are never freed here.  The
- * context owns a few small device arrays (block masks and index lists).  The zero fills are
- * enqueued on hip_stream.  128-bit accesses are used whenever block is a multiple of 4 columns, whatever
+ * context owns a few small device arrays (block masks and index lists), all allocated here: no later
+ * call allocates device memory.  hip_stream is the stream the zero fills of e and m are enqueued on
+ * (an addition to the four-call interface the method's statement suggests: the fills are device work
+ * and must be ordered with the caller's own initialisation of x).  128-bit accesses are used whenever block is a multiple of 4 columns, whatever
  * ld and the base addresses are (rows that start on 16-byte boundaries, i.e. ld % 4 == 0 and aligned
  * bases, are faster, and ld a multiple of 1024 is fastest); other block sizes run element-wise kernels with the same
  * results.  On failure *out is NULL.
@@ -103,12 +105,13 @@ int cser_destroy(cser_ctx* ctx);
 
 /*
  * Run the block selector (Definition 2; shared seed, Section 3.3) for iteration t and copy the
- * result to host memory; synchronous.  which: 0 = C_step's stream, 1 = C_reset's stream.
+ * result to host memory.  Synchronous, on a stream of the context's own (the caller's streams are not
+ * waited for); the context's state is not changed.  which: 0 = C_step's stream, 1 = C_reset's stream.
  *   idx_host   host, >= k entries or NULL: the chosen block ids in draw order pi(0..k-1)
  *   mask_host  host, B bytes or NULL: 1 where the block is chosen
  *   k_out      host or NULL: receives k
  */
-int cser_select_blocks(cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host, uint8_t* mask_host,
+int cser_select_blocks(const cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host, uint8_t* mask_host,
                        uint32_t* k_out);
 
 /* Sizes derived from the configuration: B, k_step = ceil(B/R_step), k_reset = ceil(B/R_reset). */
@@ -137,42 +140,15 @@ int cser_get_step(const cser_ctx* ctx, uint64_t* t);
 int cser_set_step(cser_ctx* ctx, uint64_t t);
 
 /*
- * Per-kernel timing.  When enabled, every launch of the fused-step kernel (which = 0) and of the
- * reset kernel (which = 1) is bracketed by HIP events on the launch stream; cser_profile_read
- * waits for the recorded events, adds their elapsed times and launch counts to running totals,
- * returns the totals and recycles the events.  At most 4096 launches per kind are held between
- * reads; later ones go untimed.
+ * n iterations in one call: the same as calling cser_step(ctx, g_list[0], hip_stream), ...,
+ * cser_step(ctx, g_list[n-1], hip_stream) one after the other (Algorithm 3's loop over t with the
+ * gradients already known, e.g. a recorded run that is replayed).  Meant for small d, where the
+ * time of an iteration is the host's cost of making the call rather than the kernel's.
+ *   g_list  host array of n device pointers, each [W][ld] fp32, read-only.
+ * Stops at the first failing iteration and returns its status; *done (host, may be NULL) receives
+ * the number of iterations enqueued.
  */
-int cser_profile_enable(cser_ctx* ctx, int on);
-int cser_profile_read(cser_ctx* ctx, int which, double* total_ms, uint64_t* launches);
-int cser_profile_clear(cser_ctx* ctx);
-
-/*
- * Launch shape of the fused-step kernel, for measurement sweeps; results do not depend on it.
- *   key 4  kernel variant: 1 (default) = row-split, a workgroup owns one worker's row over a tile of
- *          columns, tiles vary fastest with the workgroup id; 2 = row-split, workers vary fastest;
- *          0 = a lane walks all W workers for its 4 columns
- *   key 3  workgroup size: 64 (default), 128, 256, 512 or 1024
- *   key 1  -1 (default) = non-temporal loads/stores unless all state fits 256 MiB, 1 = always, 0 = never,
- *          2 / 3 = loads only / stores only
- *   key 5  row-split variants: 4-column groups per lane, 1 (default), 2 or 4
- *   key 6  1 (default) = on iterations with t mod H = 0 the error reset runs inside the fused-step kernel
- *          (x and e of the reset blocks make one trip instead of two); 0 = separate reset kernel
- *   key 7  bytes of (unused) dynamic LDS per workgroup, 0 .. 65536: caps workgroups per CU; -1 (default) = 8192,
- *          7168 or 0 for 4, 3 or 2 load streams per wavefront
- *   key 8  1 (default) = for W a power of two <= 64 the blocks that need the worker mean are shared out over the W
- *          workgroups of a tile (in-wavefront ordered sums); 0 = worker 0's workgroup walks all rows for them
- *   key 0  variant 0: workgroup cap (0 = one group per lane; n > 0 = at most n workgroups, lanes loop)
- *   key 2  variant 0: workers whose loads are issued together (1, 2, 4 or 8)
- */
-int cser_set_tuning(cser_ctx* ctx, int key, int64_t value);
-
-/*
- * Practical bandwidth ceiling: a plain copy kernel dst[i] = src[i] over n_bytes (device pointers,
- * 16-byte aligned, n_bytes a multiple of 16), enqueued on hip_stream.  Used by the benchmark to
- * report what the same access width achieves with no arithmetic.
- */
-int cser_copy_probe(void* dst, const void* src, uint64_t n_bytes, void* hip_stream);
+int cser_step_many(cser_ctx* ctx, const float* const* g_list, uint32_t n, void* hip_stream, uint32_t* done);
 
 const char* cser_strerror(int status);
 const char* cser_last_hip_error(void); /* text of the last HIP error seen by this thread, "" if none */

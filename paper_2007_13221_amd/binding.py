@@ -1,4 +1,5 @@
-"""Thin ctypes binding of the C ABI in include/cser.h: same names, argument marshalling only.
+"""Thin ctypes binding of the C ABI in include/cser.h (and of the measurement entry points in
+include/cser_measure.h): same names, argument marshalling only.
 
 Every step of the update runs in the HIP kernels of libcser_hip.so; this module never computes
 anything and has no fallback: if the library is missing or does not load, the first call raises.
@@ -14,11 +15,16 @@ LIBRARY = os.path.join(_HERE, "libcser_hip.so")
 
 CSER_OK, CSER_EINVAL, CSER_EALIGN, CSER_ENOMEM, CSER_EHIP, CSER_ERANGE = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("cser_create", "cser_step", "cser_error_reset", "cser_destroy", "cser_select_blocks",
+EXPORTS = ("cser_create", "cser_step", "cser_step_many", "cser_error_reset", "cser_destroy", "cser_select_blocks",
            "cser_preset_csea", "cser_preset_cser_pl", "cser_overall_ratio",
-           "cser_block_counts", "cser_set_lr", "cser_get_step", "cser_set_step", "cser_profile_enable",
-           "cser_profile_read", "cser_profile_clear", "cser_set_tuning", "cser_copy_probe", "cser_strerror",
-           "cser_last_hip_error")
+           "cser_block_counts", "cser_set_lr", "cser_get_step", "cser_set_step", "cser_strerror", "cser_last_hip_error")
+MEASURE_EXPORTS = ("cser_profile_enable", "cser_profile_read", "cser_profile_clear", "cser_set_tuning",
+                   "cser_measure_counters", "cser_measure_residency", "cser_copy_probe")
+
+# cser_tuning_key
+CSER_TUNE_KERNEL, CSER_TUNE_NONTEMPORAL, CSER_TUNE_FUSE_RESET = 0, 1, 2
+CSER_TUNE_TILE_WAVES_PER_CU, CSER_TUNE_SHARED_GROUPS_PER_CU = 3, 4
+KERNEL_AUTO, KERNEL_TILE, KERNEL_SHARED, KERNEL_GENERAL = 0, 1, 2, 3
 
 
 class cser_config(ctypes.Structure):
@@ -26,6 +32,17 @@ class cser_config(ctypes.Structure):
                 ("block", ctypes.c_uint32), ("R_step", ctypes.c_uint32), ("R_reset", ctypes.c_uint32),
                 ("H", ctypes.c_uint32), ("lr", ctypes.c_float), ("momentum", ctypes.c_float),
                 ("seed", ctypes.c_uint64)]
+
+
+class cser_counters(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in ("steps", "window_draws", "resets_fused", "resets_separate",
+                                               "launches_tile", "launches_shared", "launches_general")]
+
+
+class cser_residency(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in ("tile_lds", "tile_groups_per_cu", "shared_lds", "shared_groups_per_cu",
+                                               "shared_reset_lds", "shared_reset_groups_per_cu", "reset_lds",
+                                               "reset_groups_per_cu")]
 
 
 class CSERError(RuntimeError):
@@ -52,6 +69,7 @@ def _lib():
         vp, u64, u32, i64 = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int64
         L.cser_create.argtypes = [ctypes.POINTER(cser_config), vp, vp, vp, vp, ctypes.POINTER(vp)]
         L.cser_step.argtypes = [vp, vp, vp]
+        L.cser_step_many.argtypes = [vp, vp, u32, vp, ctypes.POINTER(u32)]
         L.cser_error_reset.argtypes = [vp, vp]
         L.cser_destroy.argtypes = [vp]
         L.cser_select_blocks.argtypes = [vp, ctypes.c_int, u64, vp, vp, ctypes.POINTER(u32)]
@@ -67,11 +85,13 @@ def _lib():
         L.cser_profile_clear.argtypes = [vp]
         L.cser_set_tuning.argtypes = [vp, ctypes.c_int, i64]
         L.cser_copy_probe.argtypes = [vp, vp, u64, vp]
+        L.cser_measure_counters.argtypes = [vp, ctypes.POINTER(cser_counters)]
+        L.cser_measure_residency.argtypes = [vp, ctypes.POINTER(cser_residency)]
         L.cser_strerror.argtypes = [ctypes.c_int]
         L.cser_strerror.restype = ctypes.c_char_p
         L.cser_last_hip_error.argtypes = []
         L.cser_last_hip_error.restype = ctypes.c_char_p
-        for name in EXPORTS:
+        for name in EXPORTS + MEASURE_EXPORTS:
             if name not in ("cser_strerror", "cser_last_hip_error"):
                 getattr(L, name).restype = ctypes.c_int
         _LIB = L
@@ -112,6 +132,23 @@ def cser_create(cfg: cser_config, x, e, m, stream=None):
 
 def cser_step(ctx, g, stream=None):
     _check(_lib().cser_step(ctx, _ptr(g), _stream(stream)), "cser_step")
+
+
+def cser_step_many(ctx, grads, stream=None):
+    """grads: a sequence of device tensors (or raw addresses), one per iteration; or a prepared
+    (ctypes pointer array, n) pair from gradient_list()."""
+    if not (isinstance(grads, tuple) and len(grads) == 2 and isinstance(grads[1], int)):
+        grads = gradient_list(grads)
+    arr, n = grads
+    done = ctypes.c_uint32()
+    _check(_lib().cser_step_many(ctx, arr, n, _stream(stream), ctypes.byref(done)), "cser_step_many")
+    return done.value
+
+
+def gradient_list(grads):
+    """The host array of device pointers cser_step_many takes, built once for repeated use."""
+    arr = (ctypes.c_void_p * len(grads))(*[_ptr(g) for g in grads])
+    return arr, len(grads)
 
 
 def cser_error_reset(ctx, stream=None):
@@ -190,6 +227,18 @@ def cser_set_tuning(ctx, key, value):
     _check(_lib().cser_set_tuning(ctx, int(key), int(value)), "cser_set_tuning")
 
 
+def cser_measure_counters(ctx):
+    c = cser_counters()
+    _check(_lib().cser_measure_counters(ctx, ctypes.byref(c)), "cser_measure_counters")
+    return {n: getattr(c, n) for n, _ in cser_counters._fields_}
+
+
+def cser_measure_residency(ctx):
+    r = cser_residency()
+    _check(_lib().cser_measure_residency(ctx, ctypes.byref(r)), "cser_measure_residency")
+    return {n: getattr(r, n) for n, _ in cser_residency._fields_}
+
+
 def cser_copy_probe(dst, src, n_bytes, stream=None):
     _check(_lib().cser_copy_probe(_ptr(dst), _ptr(src), int(n_bytes), _stream(stream)), "cser_copy_probe")
 
@@ -217,6 +266,9 @@ class CSER:
 
     def step(self, g, stream=None):
         cser_step(self.ctx, g, stream)
+
+    def step_many(self, grads, stream=None):
+        return cser_step_many(self.ctx, grads, stream)
 
     def error_reset(self, stream=None):
         cser_error_reset(self.ctx, stream)

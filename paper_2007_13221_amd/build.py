@@ -11,7 +11,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 SOURCES = [os.path.join(CSRC, "cser_kernels.hip"), os.path.join(CSRC, "cser_api.hip")]
-HEADERS = [os.path.join(CSRC, "cser_internal.h"), os.path.join(os.path.dirname(HERE), "include", "cser.h")]
+HEADERS = [os.path.join(CSRC, "cser_internal.h"), os.path.join(os.path.dirname(HERE), "include", "cser.h"),
+           os.path.join(os.path.dirname(HERE), "include", "cser_measure.h")]
 LIBRARY = os.path.join(HERE, "libcser_hip.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",

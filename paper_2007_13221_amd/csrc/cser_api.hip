@@ -1,8 +1,8 @@
-// C ABI of the CSER update (declared in include/cser.h): argument checks, the context, the
-// iteration counter of Algorithm 3 and the order in which the kernels are enqueued.  No arithmetic
-// of the method happens on the host.
+// C ABI of the CSER update (declared in include/cser.h; measurement entry points in include/cser_measure.h):
+// argument checks, the context, the iteration counter of Algorithm 3 and the order in which the kernels are
+// enqueued.  No arithmetic of the method happens on the host.
 
-#include "../../include/cser.h"
+#include "../../include/cser_measure.h"
 #include "cser_internal.h"
 
 #include <cmath>
@@ -45,6 +45,23 @@ bool on_its_device(int device) {
   return device < 0 || (hipGetDevice(&current) == hipSuccess && current == device);
 }
 
+// Non-temporal accesses pay once the state no longer fits the 256 MiB last-level cache (measured +10 % on the
+// large workload); a smaller working set is better served by ordinary accesses, because x, e, m come back in
+// the next iteration (+7 % at 110-250 MB).
+bool wants_nontemporal(const cser_config& c, bool has_e, bool has_m, int setting) {
+  if (setting >= 0) return setting != 0;
+  const uint64_t arrays = 2u + (has_e ? 1u : 0u) + (has_m ? 1u : 0u);
+  return static_cast<uint64_t>(c.W) * c.ld * 4u * arrays > (256ull << 20);
+}
+
+// Expected share of the blocks that need the worker mean in one launch: those C_step chose, and on an iteration
+// whose reset is fused in, those C_reset chose (the two choices are independent).
+double sync_share(uint64_t B, uint32_t k_step, uint32_t k_reset, bool fused_reset) {
+  const double cs = static_cast<double>(k_step) / static_cast<double>(B);
+  const double cr = fused_reset ? static_cast<double>(k_reset) / static_cast<double>(B) : 0.0;
+  return cs + cr - cs * cr;
+}
+
 }  // namespace
 
 struct cser_ctx {
@@ -57,6 +74,8 @@ struct cser_ctx {
   uint32_t k_step, k_reset;
   uint64_t t;
   bool vector_layout;        // block is a multiple of 4 columns: a 4-column group never straddles two blocks
+  bool nontemporal;
+  cser::Caps caps;
   uint8_t* mask_step;        // device, window * B bytes: C_step's masks for iterations win_t0 .. win_t0 + win_n - 1
   uint32_t window;           // iterations drawn per selector launch
   uint64_t win_t0;
@@ -67,12 +86,14 @@ struct cser_ctx {
   uint8_t* mask_reset_win;   // device, window * B bytes: C_reset's masks of the reset iterations inside the window
   uint64_t win_reset_t0;     // first reset iteration (multiple of H) in the window
   uint32_t win_reset_n;      // number of reset iterations in the window
-  uint32_t* idx_reset;       // device, max(k_reset, 1) entries
+  uint32_t* idx_reset;       // device, max(k_reset, 1) entries: the reset's block list in increasing order
   uint8_t* mask_query;       // device scratch of cser_select_blocks, B bytes
-  uint32_t* idx_query;       // device scratch of cser_select_blocks, B entries (lazily allocated)
+  uint32_t* idx_query;       // device scratch of cser_select_blocks, max(k_step, k_reset, 1) entries
+  hipStream_t query_stream;  // cser_select_blocks runs here
   cser::Tuning tuning;
   bool profiling;
   Timer timers[2];
+  cser_counters counters;
 };
 
 namespace {
@@ -126,6 +147,7 @@ void free_device_arrays(cser_ctx* ctx) {
   if (ctx->idx_reset) (void)hipFree(ctx->idx_reset);
   if (ctx->mask_query) (void)hipFree(ctx->mask_query);
   if (ctx->idx_query) (void)hipFree(ctx->idx_query);
+  if (ctx->query_stream) (void)hipStreamDestroy(ctx->query_stream);
   for (Timer& tm : ctx->timers) {
     for (hipEvent_t ev : tm.begin) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : tm.end) (void)hipEventDestroy(ev);
@@ -143,6 +165,52 @@ int validate(const cser_config* c, const float* x, const float* e, const float* 
   const uint64_t B = ceil_div(c->d, c->block);
   if (B > 0xFFFFFFFFull) return CSER_ERANGE;
   if (c->d / 4 > 0xFFFFFFFFull) return CSER_ERANGE;
+  if (c->block % 4 != 0 && c->d > 0xFFFFFFFFull) return CSER_ERANGE;   // the element-wise kernels index columns with 32 bits
+  // one-wavefront workgroups: one per (worker, 256-column tile), at most 2^31 - 1 of them in a launch
+  if (c->W <= 64 && ceil_div(c->d / 4, 64) * c->W > 0x7FFFFFFFull) return CSER_ERANGE;
+  return CSER_OK;
+}
+
+int refresh_launch_shapes(cser_ctx* ctx) {
+  ctx->nontemporal = wants_nontemporal(ctx->cfg, ctx->e != nullptr, ctx->m != nullptr, ctx->tuning.nontemporal);
+  if (!ctx->vector_layout) {
+    ctx->caps = cser::Caps();
+    return CSER_OK;
+  }
+  CSER_HIP(cser::resolve_caps(ctx->cfg.W, ctx->e != nullptr, ctx->m != nullptr, ctx->nontemporal, ctx->tuning, &ctx->caps));
+  return CSER_OK;
+}
+
+// The masks of iterations t .. t + window - 1 (stopping at the largest 64-bit t), and C_reset's masks of the
+// reset iterations (multiples of H) among them, for the fused reset.
+int draw_window(cser_ctx* ctx, uint64_t t, hipStream_t s) {
+  ctx->win_n = 0;   // nothing usable until the draw below has been enqueued completely
+  ctx->win_reset_n = 0;
+  uint32_t count = ctx->window;
+  if (UINT64_MAX - t < count - 1) count = static_cast<uint32_t>(UINT64_MAX - t) + 1u;
+  CSER_HIP(cser::launch_selector(ctx->cfg.seed, 0u, t, 1u, count, static_cast<uint32_t>(ctx->B), ctx->k_step,
+                                 ctx->mask_step, nullptr, s));
+  uint32_t reset_n = 0;
+  uint64_t reset_t0 = 0;
+  const uint64_t H = ctx->cfg.H;
+  if (H > 0 && ctx->tuning.fuse_reset) {
+    const uint64_t last = t + (count - 1);
+    const uint64_t rem = t % H;
+    const uint64_t gap = rem == 0 ? 0 : H - rem;
+    if (gap <= last - t) {
+      reset_t0 = t + gap;
+      reset_n = static_cast<uint32_t>((last - reset_t0) / H) + 1u;
+      CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, reset_t0, H, reset_n, static_cast<uint32_t>(ctx->B), ctx->k_reset,
+                                     ctx->mask_reset_win, nullptr, s));
+    }
+  }
+  CSER_HIP(hipEventRecord(ctx->win_done, s));
+  ctx->win_t0 = t;
+  ctx->win_n = count;
+  ctx->win_reset_t0 = reset_t0;
+  ctx->win_reset_n = reset_n;
+  ctx->win_stream = s;
+  ctx->counters.window_draws += 1;
   return CSER_OK;
 }
 
@@ -168,11 +236,8 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
   ctx->k_reset = static_cast<uint32_t>(ceil_div(ctx->B, cfg->R_reset));
   ctx->t = 0;
   ctx->vector_layout = cfg->block % 4 == 0;
-  if (!ctx->vector_layout && cfg->d > 0xFFFFFFFFull) {
-    delete ctx;
-    return CSER_ERANGE;   // the element-wise kernels index columns with 32 bits
-  }
   ctx->profiling = false;
+  std::memset(&ctx->counters, 0, sizeof(ctx->counters));
 
   // C_step's choice is a pure function of (seed, t): draw up to 32 iterations per selector launch
   // (fewer when B is so large that the masks would pass 64 MiB), so its latency is paid once per window
@@ -181,21 +246,30 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
   ctx->win_n = 0;
   ctx->win_t0 = 0;
   ctx->win_stream = nullptr;
+  ctx->win_reset_t0 = 0;
+  ctx->win_reset_n = 0;
+  const uint32_t k_max = ctx->k_step > ctx->k_reset ? ctx->k_step : ctx->k_reset;
   hipError_t err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_step), static_cast<uint64_t>(ctx->window) * ctx->B);
   if (err == hipSuccess) err = hipEventCreateWithFlags(&ctx->win_done, hipEventDisableTiming);
   if (err == hipSuccess && cfg->H > 0)
     err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_reset_win), static_cast<uint64_t>(ctx->window) * ctx->B);
-  ctx->win_reset_t0 = 0;
-  ctx->win_reset_n = 0;
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_reset), ctx->B);
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_query), ctx->B);
   if (err == hipSuccess)
     err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_reset), sizeof(uint32_t) * (ctx->k_reset ? ctx->k_reset : 1u));
+  if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_query), sizeof(uint32_t) * (k_max ? k_max : 1u));
+  if (err == hipSuccess) err = hipStreamCreateWithFlags(&ctx->query_stream, hipStreamNonBlocking);
   if (err != hipSuccess) {
     free_device_arrays(ctx);
     delete ctx;
     if (err == hipErrorOutOfMemory) return CSER_ENOMEM;
-    return hip_failed(err, "hipMalloc");
+    return hip_failed(err, "allocating the context's device arrays");
+  }
+  int rc = refresh_launch_shapes(ctx);
+  if (rc != CSER_OK) {
+    free_device_arrays(ctx);
+    delete ctx;
+    return rc;
   }
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -215,8 +289,10 @@ int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
   if (!ctx || !on_its_device(ctx->device)) return CSER_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (ctx->k_reset == 0) return CSER_OK;
+  // the mask from the blocks' side, then the chosen ids in increasing order: the kernel sweeps the rows forwards
   CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, 0u, 1u, static_cast<uint32_t>(ctx->B), ctx->k_reset,
-                                 ctx->mask_reset, ctx->idx_reset, s));
+                                 ctx->mask_reset, nullptr, s));
+  CSER_HIP(cser::launch_ordered_list(ctx->mask_reset, static_cast<uint32_t>(ctx->B), ctx->k_reset, ctx->idx_reset, s));
   cser::ResetParams p;
   p.x = ctx->x;
   p.e = ctx->e;
@@ -229,7 +305,8 @@ int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
   bool timed = false;
   int rc = record_begin(ctx, 1, s, &timed);
   if (rc != CSER_OK) return rc;
-  CSER_HIP(cser::launch_reset(p, ctx->mask_reset, ctx->vector_layout, s));
+  CSER_HIP(cser::launch_reset(p, ctx->mask_reset, ctx->vector_layout, ctx->nontemporal, ctx->tuning, ctx->caps, s));
+  ctx->counters.resets_separate += 1;
   return record_end(ctx, 1, s, timed);
 }
 
@@ -239,29 +316,8 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const uint64_t t = ctx->t + 1;
   if (ctx->win_n == 0 || t < ctx->win_t0 || t - ctx->win_t0 >= ctx->win_n) {
-    // the masks of iterations t .. t + window - 1 (stopping at the largest 64-bit t)
-    uint32_t count = ctx->window;
-    if (UINT64_MAX - t < count - 1) count = static_cast<uint32_t>(UINT64_MAX - t) + 1u;
-    CSER_HIP(cser::launch_selector(ctx->cfg.seed, 0u, t, 1u, count, static_cast<uint32_t>(ctx->B), ctx->k_step,
-                                   ctx->mask_step, nullptr, s));
-    // and C_reset's masks of the reset iterations (multiples of H) among them, for the fused reset
-    ctx->win_reset_n = 0;
-    const uint64_t H = ctx->cfg.H;
-    if (H > 0 && ctx->tuning.fuse_reset) {
-      const uint64_t last = t + (count - 1);
-      const uint64_t rem = t % H;
-      const uint64_t gap = rem == 0 ? 0 : H - rem;
-      if (gap <= last - t) {
-        ctx->win_reset_t0 = t + gap;
-        ctx->win_reset_n = static_cast<uint32_t>((last - ctx->win_reset_t0) / H) + 1u;
-        CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->win_reset_t0, H, ctx->win_reset_n,
-                                       static_cast<uint32_t>(ctx->B), ctx->k_reset, ctx->mask_reset_win, nullptr, s));
-      }
-    }
-    CSER_HIP(hipEventRecord(ctx->win_done, s));
-    ctx->win_t0 = t;
-    ctx->win_n = count;
-    ctx->win_stream = s;
+    const int rc = draw_window(ctx, t, s);
+    if (rc != CSER_OK) return rc;
   } else if (s != ctx->win_stream) {
     CSER_HIP(hipStreamWaitEvent(s, ctx->win_done, 0));   // drawn on another stream: order after it
   }
@@ -284,11 +340,29 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
   bool timed = false;
   int rc = record_begin(ctx, 0, s, &timed);
   if (rc != CSER_OK) return rc;
-  CSER_HIP(cser::launch_step(p, ctx->vector_layout, ctx->tuning, s));
+  int used = 0;
+  CSER_HIP(cser::launch_step(p, ctx->vector_layout, ctx->nontemporal, ctx->tuning, ctx->caps,
+                             sync_share(ctx->B, ctx->k_step, ctx->k_reset, fused), &used, s));
   rc = record_end(ctx, 0, s, timed);
   if (rc != CSER_OK) return rc;
   ctx->t = t;
+  ctx->counters.steps += 1;
+  if (used == cser::kKernelTile) ctx->counters.launches_tile += 1;
+  else if (used == cser::kKernelShared) ctx->counters.launches_shared += 1;
+  else ctx->counters.launches_general += 1;
+  if (fused) ctx->counters.resets_fused += 1;
   if (reset_now && !fused) return cser_error_reset(ctx, hip_stream);
+  return CSER_OK;
+}
+
+int cser_step_many(cser_ctx* ctx, const float* const* g_list, uint32_t n, void* hip_stream, uint32_t* done) {
+  if (done) *done = 0;
+  if (!ctx || (!g_list && n > 0)) return CSER_EINVAL;
+  for (uint32_t i = 0; i < n; ++i) {
+    const int rc = cser_step(ctx, g_list[i], hip_stream);
+    if (rc != CSER_OK) return rc;
+    if (done) *done = i + 1;
+  }
   return CSER_OK;
 }
 
@@ -299,21 +373,17 @@ int cser_destroy(cser_ctx* ctx) {
   return CSER_OK;
 }
 
-int cser_select_blocks(cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host, uint8_t* mask_host,
+int cser_select_blocks(const cser_ctx* ctx, int which, uint64_t t, uint32_t* idx_host, uint8_t* mask_host,
                        uint32_t* k_out) {
-  if (!ctx || (which != 0 && which != 1)) return CSER_EINVAL;
+  if (!ctx || (which != 0 && which != 1) || !on_its_device(ctx->device)) return CSER_EINVAL;
   const uint32_t k = which == 0 ? ctx->k_step : ctx->k_reset;
   if (k_out) *k_out = k;
-  if (!ctx->idx_query) {
-    hipError_t err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_query), sizeof(uint32_t) * ctx->B);
-    if (err == hipErrorOutOfMemory) return CSER_ENOMEM;
-    if (err != hipSuccess) return hip_failed(err, "hipMalloc");
-  }
+  hipStream_t s = ctx->query_stream;
   CSER_HIP(cser::launch_selector(ctx->cfg.seed, static_cast<uint32_t>(which), t, 0u, 1u, static_cast<uint32_t>(ctx->B), k,
-                                 ctx->mask_query, ctx->idx_query, nullptr));
-  CSER_HIP(hipStreamSynchronize(nullptr));
-  if (mask_host) CSER_HIP(hipMemcpy(mask_host, ctx->mask_query, ctx->B, hipMemcpyDeviceToHost));
-  if (idx_host && k) CSER_HIP(hipMemcpy(idx_host, ctx->idx_query, sizeof(uint32_t) * k, hipMemcpyDeviceToHost));
+                                 ctx->mask_query, ctx->idx_query, s));
+  if (mask_host) CSER_HIP(hipMemcpyAsync(mask_host, ctx->mask_query, ctx->B, hipMemcpyDeviceToHost, s));
+  if (idx_host && k) CSER_HIP(hipMemcpyAsync(idx_host, ctx->idx_query, sizeof(uint32_t) * k, hipMemcpyDeviceToHost, s));
+  CSER_HIP(hipStreamSynchronize(s));
   return CSER_OK;
 }
 
@@ -365,6 +435,22 @@ int cser_set_step(cser_ctx* ctx, uint64_t t) {
   return CSER_OK;
 }
 
+const char* cser_strerror(int status) {
+  switch (status) {
+    case CSER_OK: return "ok";
+    case CSER_EINVAL: return "invalid argument";
+    case CSER_EALIGN: return "misaligned pointer or size";
+    case CSER_ENOMEM: return "out of memory";
+    case CSER_EHIP: return "HIP runtime error (see cser_last_hip_error)";
+    case CSER_ERANGE: return "size beyond the supported range";
+    default: return "unknown status";
+  }
+}
+
+const char* cser_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+// ---------------------------------------------------------------- measurement only (cser_measure.h)
+
 int cser_profile_enable(cser_ctx* ctx, int on) {
   if (!ctx) return CSER_EINVAL;
   ctx->profiling = on != 0;
@@ -393,46 +479,61 @@ int cser_profile_clear(cser_ctx* ctx) {
 }
 
 int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
-  if (!ctx) return CSER_EINVAL;
+  if (!ctx || !on_its_device(ctx->device)) return CSER_EINVAL;
+  cser::Tuning next = ctx->tuning;
   switch (key) {
-    case 0:
-      if (value < 0 || value > 0x7FFFFFFF) return CSER_EINVAL;
-      ctx->tuning.wg_cap = value;
-      return CSER_OK;
-    case 1:
-      if (value < -1 || value > 3) return CSER_EINVAL;
-      ctx->tuning.nontemporal = static_cast<int>(value);
-      return CSER_OK;
-    case 2:
-      if (value != 1 && value != 2 && value != 4 && value != 8) return CSER_EINVAL;
-      ctx->tuning.batch = static_cast<int>(value);
-      return CSER_OK;
-    case 3:
-      if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return CSER_EINVAL;
-      ctx->tuning.threads = static_cast<int>(value);
-      return CSER_OK;
-    case 4:
+    case CSER_TUNE_KERNEL:
       if (value < 0 || value > 3) return CSER_EINVAL;
-      ctx->tuning.variant = static_cast<int>(value);
-      return CSER_OK;
-    case 5:
-      if (value != 1 && value != 2 && value != 4) return CSER_EINVAL;
-      ctx->tuning.cols_per_lane = static_cast<int>(value);
-      return CSER_OK;
-    case 8:
-      ctx->tuning.balanced = value != 0;
-      return CSER_OK;
-    case 7:
-      if (value < -1 || value > 65536) return CSER_EINVAL;
-      ctx->tuning.lds_bytes = static_cast<int>(value);
-      return CSER_OK;
-    case 6:
-      ctx->tuning.fuse_reset = value != 0;
-      ctx->win_n = 0;   // the window is redrawn with (or without) C_reset's masks
-      return CSER_OK;
+      next.kernel = static_cast<int>(value);
+      break;
+    case CSER_TUNE_NONTEMPORAL:
+      if (value < -1 || value > 1) return CSER_EINVAL;
+      next.nontemporal = static_cast<int>(value);
+      break;
+    case CSER_TUNE_FUSE_RESET:
+      next.fuse_reset = value != 0;
+      break;
+    case CSER_TUNE_TILE_WAVES_PER_CU:
+      if (value < -1 || value > 64) return CSER_EINVAL;
+      next.tile_waves_per_cu = static_cast<int>(value);
+      break;
+    case CSER_TUNE_SHARED_GROUPS_PER_CU:
+      if (value < -1 || value > 64) return CSER_EINVAL;
+      next.shared_groups_per_cu = static_cast<int>(value);
+      break;
     default:
       return CSER_EINVAL;
   }
+  const cser::Tuning before = ctx->tuning;
+  ctx->tuning = next;
+  const int rc = refresh_launch_shapes(ctx);
+  if (rc != CSER_OK) {
+    ctx->tuning = before;
+    (void)refresh_launch_shapes(ctx);
+    return rc;
+  }
+  ctx->win_n = 0;   // the window is redrawn with (or without) C_reset's masks
+  return CSER_OK;
+}
+
+int cser_measure_counters(const cser_ctx* ctx, cser_counters* out) {
+  if (!ctx || !out) return CSER_EINVAL;
+  *out = ctx->counters;
+  return CSER_OK;
+}
+
+int cser_measure_residency(const cser_ctx* ctx, cser_residency* out) {
+  if (!ctx || !out) return CSER_EINVAL;
+  const cser::Caps& c = ctx->caps;
+  out->tile_lds = c.tile_lds;
+  out->tile_groups_per_cu = c.tile_resident;
+  out->shared_lds = c.shared_lds;
+  out->shared_groups_per_cu = c.shared_resident;
+  out->shared_reset_lds = c.shared_reset_lds;
+  out->shared_reset_groups_per_cu = c.shared_reset_resident;
+  out->reset_lds = c.reset_lds;
+  out->reset_groups_per_cu = c.reset_resident;
+  return CSER_OK;
 }
 
 int cser_copy_probe(void* dst, const void* src, uint64_t n_bytes, void* hip_stream) {
@@ -442,19 +543,5 @@ int cser_copy_probe(void* dst, const void* src, uint64_t n_bytes, void* hip_stre
   CSER_HIP(cser::launch_copy(dst, src, n_bytes, static_cast<hipStream_t>(hip_stream)));
   return CSER_OK;
 }
-
-const char* cser_strerror(int status) {
-  switch (status) {
-    case CSER_OK: return "ok";
-    case CSER_EINVAL: return "invalid argument";
-    case CSER_EALIGN: return "misaligned pointer or size";
-    case CSER_ENOMEM: return "out of memory";
-    case CSER_EHIP: return "HIP runtime error (see cser_last_hip_error)";
-    case CSER_ERANGE: return "size beyond the supported range";
-    default: return "unknown status";
-  }
-}
-
-const char* cser_last_hip_error(void) { return g_last_hip_error.c_str(); }
 
 }  // extern "C"

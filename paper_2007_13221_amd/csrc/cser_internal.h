@@ -15,7 +15,7 @@ struct StepParams {
   float* m;
   float* x;
   float* e;
-  const uint8_t* mask;  // B bytes, 1 = block chosen by C_step for this t
+  const uint8_t* mask;        // B bytes, 1 = block chosen by C_step for this t
   const uint8_t* reset_mask;  // null, or B bytes: blocks C_reset chose at this t; the reset is then done in the same pass
   uint64_t ld;
   uint64_t d;
@@ -36,29 +36,52 @@ struct ResetParams {
   uint32_t k;
 };
 
-struct Tuning {
-  int64_t wg_cap = 0;   // 0: one 4-column group per lane; > 0: at most this many workgroups
-  int nontemporal = -1;  // -1 by working-set size, 0 none, 1 loads and stores, 2 loads only, 3 stores only (variant 0: zero / non-zero)
-  int batch = 4;        // workers whose loads are issued together
-  int threads = 64;     // workgroup size of the fused-step kernel (one wavefront: measured best)
-  int variant = 1;      // 0: a lane walks all workers; row-split: 1 tiles fastest, 2 workers fastest, 3 per-XCD sweeps
-  int lds_bytes = -1;   // dynamic LDS requested per workgroup and never touched (occupancy cap); -1: by stream count
-  int balanced = 1;     // W a power of two <= 64: every workgroup of a tile takes 1/W of its synchronised work
-  int fuse_reset = 1;   // on reset iterations do the error reset inside the fused-step kernel
-  int cols_per_lane = 1;  // row-split variants: 4-column groups per lane
+// Which fused-step kernel runs (all give the same bits).
+enum StepKernel {
+  kKernelAuto = 0,     // by worker count and by the share of blocks that need the worker mean this iteration
+  kKernelTile = 1,     // one-wavefront workgroups, one worker's row per workgroup (W <= 64)
+  kKernelShared = 2,   // W-wavefront workgroups, worker sums staged in LDS (W <= 16)
+  kKernelGeneral = 3   // a lane walks all workers (any W, any block size)
 };
+
+struct Tuning {
+  int kernel = kKernelAuto;
+  int nontemporal = -1;     // -1 by working-set size, 0 ordinary accesses, 1 non-temporal loads and stores
+  int fuse_reset = 1;       // on reset iterations do the error reset inside the fused-step kernel
+  int tile_waves_per_cu = -1;    // tile kernel: most resident one-wavefront workgroups per CU; -1 by stream count, 0 no cap
+  int shared_groups_per_cu = -1; // LDS-shared kernels: most resident workgroups per CU; -1 by worker count, 0 no cap
+};
+
+// Residency caps of the streaming kernels.  What the memory system rewards is a bounded number of requests in
+// flight per CU; a workgroup's dynamic LDS request is the one launch parameter that bounds residency, so the
+// request is chosen -- with the runtime's own occupancy calculator, for the device at hand -- as the smallest
+// one under which no more than the wanted number of workgroups fit a CU.  `*_resident` is what the calculator
+// reports for the chosen request (what a launch gets), 0 if it could not be queried.
+struct Caps {
+  uint32_t tile_lds = 0, tile_resident = 0;
+  uint32_t shared_lds = 0, shared_resident = 0;         // step kernel without a fused reset
+  uint32_t shared_reset_lds = 0, shared_reset_resident = 0;   // step kernel with a fused reset (twice the staging area)
+  uint32_t reset_lds = 0, reset_resident = 0;           // reset kernel on its own
+};
+hipError_t resolve_caps(uint32_t W, bool has_e, bool has_m, bool nontemporal, const Tuning& tune, Caps* out);
 
 // GRBS block selector (Definition 2) for the `count` iterations t0, t0 + t_stride, ...: mask[j*B + b] = 1 iff
 // block b is chosen at the j-th of them.  idx (may be null, count must be 1): idx[pi^-1(b)] = b for the k chosen.
 hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint64_t t_stride, uint32_t count, uint32_t B,
                            uint32_t k, uint8_t* mask, uint32_t* idx, hipStream_t s);
 
-// Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d).  `vectorised` requires block to be a
-// multiple of 4 columns (rows need only 4-byte alignment).
-hipError_t launch_step(const StepParams& p, bool vectorised, const Tuning& tune, hipStream_t s);
+// The chosen block ids of a mask (which holds exactly k of them) in increasing order: idx_sorted[0..k).
+hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* idx_sorted, hipStream_t s);
 
-// Error reset on the chosen blocks (idx: the k chosen ids; mask: the same choice as B bytes).
-hipError_t launch_reset(const ResetParams& p, const uint8_t* mask, bool vectorised, hipStream_t s);
+// Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d) (and the error reset when p.reset_mask is set).
+// `vectorised` requires block to be a multiple of 4 columns (rows need only 4-byte alignment).  `sync_share`:
+// expected share of the blocks that need the worker mean in this launch.  *used (may be null) receives the kernel taken.
+hipError_t launch_step(const StepParams& p, bool vectorised, bool nontemporal, const Tuning& tune, const Caps& caps,
+                       double sync_share, int* used, hipStream_t s);
+
+// Error reset on the chosen blocks (idx: the k chosen ids in increasing order; mask: the same choice as B bytes).
+hipError_t launch_reset(const ResetParams& p, const uint8_t* mask, bool vectorised, bool nontemporal, const Tuning& tune,
+                        const Caps& caps, hipStream_t s);
 
 hipError_t launch_fill_zero(float* ptr, uint64_t n, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, uint64_t n_bytes, hipStream_t s);

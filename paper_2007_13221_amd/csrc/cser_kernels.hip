@@ -1,33 +1,38 @@
 // HIP kernels of the CSER optimizer update for gfx950 (MI355X), and their launch wrappers.
 //
-//   grbs_select_kernel      the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3),
-//   grbs_scatter_kernel     from the blocks' side (inverse permutation) or from the draws' side (forward)
-//   cser_step_tile_kernel   Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass, and on
-//                           reset iterations the error reset as well (W a power of two <= 64: the default)
-//   cser_step_rows_kernel   the same for any W and other launch shapes (worker 0's workgroup walks all rows
-//                           of the blocks that need the worker mean)
-//   cser_step_kernel        the same, one lane per column group walking all workers (element-wise
-//                           fallback for unaligned layouts; also a measured alternative)
-//   cser_reset_kernel       the error-reset branch of Algorithm 3 on its own (PSync(e, C_reset), x correction)
+//   grbs_select_kernel        the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3),
+//   grbs_scatter_kernel       from the blocks' side (inverse permutation) or from the draws' side (forward)
+//   ordered_list_kernel       the chosen block ids of a mask in increasing order (for the reset kernel)
+//   cser_step_tile_kernel     Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass, and on reset
+//                             iterations the error reset as well; one-wavefront workgroups, W <= 64: the default
+//   cser_step_shared_kernel   the same with W-wavefront workgroups and the worker sums staged in LDS (W <= 16);
+//                             taken when most blocks need the worker mean
+//   cser_step_general_kernel  the same, one lane per column group walking all workers: any W, any block size
+//   cser_reset_shared_kernel  the error-reset branch of Algorithm 3 on its own (PSync(e, C_reset), x correction)
+//   cser_reset_general_kernel the same for any W and any block size
 //
-// The update is a pure stream over HBM (about 6 flops per 28 bytes), so there is no matrix-core
-// work here and nothing to stage in LDS.  States are worker-major rows [W][ld].  On a block that
-// C_step did not choose, every worker's update is independent, so the default kernel gives each
-// workgroup -- a single wavefront -- ONE worker's row over 256 columns: 4 load streams and 3 store
-// streams of 128-bit accesses, 1 KiB per stream, consecutive workgroups on consecutive tiles.
-// Only the chosen blocks (1 / R_step of them) need the worker mean.  In the default kernel the W
-// workgroups of a tile share that work: each takes 1/W of the tile's chosen column groups for all
-// workers, one worker per lane group, and the W-way sum is a fixed-order chain of wavefront
-// shuffles -- every value still makes one trip, and the order is that of a sequential evaluation.
-// In the general kernel a lane owns 4 columns and walks the worker axis itself (a private chain of
-// adds in registers).
-// What the memory system rewards, all measured: one worker per workgroup rather than all workers
-// per lane, 1 KiB tiles, rows that start on 4 KiB boundaries, non-temporal accesses once the state
-// exceeds the last-level cache, and no more than about 16-20 resident wavefronts per CU.
+// The update is a pure stream over HBM (about 6 flops per 28 bytes): no matrix-core work.  States are
+// worker-major rows [W][ld].  What the memory system rewards, all measured on the large workload:
+//   * a wavefront should read and write ONE row, one contiguous KiB per stream, and consecutive workgroups
+//     should sweep that row linearly: 6.4-6.8 TB/s for 2 to 7 streams.  Wavefronts of one workgroup (or one CU)
+//     that work on W different rows at once reach 5.6-6.0, a wavefront that itself touches 2 / 4 / 8 rows per
+//     access (512 / 256 / 128 contiguous bytes each) 5.6 / 5.0 / 4.4;
+//   * non-temporal accesses once the state exceeds the last-level cache, and a bounded number of resident
+//     wavefronts per CU (see resolve_caps).
+// On a block that C_step did not choose every worker's update is independent, so the default kernel gives each
+// one-wavefront workgroup one worker's row over 256 columns.  Only the chosen blocks (1 / R_step of them) need
+// the worker mean, which inevitably brings W rows together: in the default kernel the W workgroups of a tile
+// share that work (each takes 1/W of the tile's chosen column groups for all workers, one worker per lane group,
+// the W-way sum being a fixed-order chain of wavefront shuffles); when half of the blocks or more are chosen,
+// the LDS-shared kernel, whose every access is still a contiguous KiB of one row, is the faster one.
 //
-// Build with -ffp-contract=off: every fused multiply-add below is written out, nothing else fuses.
+// Arithmetic, identical in every kernel: beta*m+g and beta*m_new+g are single fused multiply-adds, eta multiplies
+// the rounded result, the worker sum starts from worker 0's value and adds workers 1 .. W-1 in order, the mean is
+// that sum divided by W (true division).  Build with -ffp-contract=off: nothing else fuses.
 
 #include "cser_internal.h"
+
+#include <type_traits>
 
 namespace cser {
 namespace {
@@ -74,6 +79,14 @@ __device__ __forceinline__ void store_pack(float* p, const Pack<V>& r) {
   }
 }
 
+template <int V>
+__device__ __forceinline__ Pack<V> zero_pack() {
+  Pack<V> r;
+#pragma unroll
+  for (int c = 0; c < V; ++c) r.v[c] = 0.0f;
+  return r;
+}
+
 // Get_p (Appendix A.4): m <- beta m + g, p <- eta (beta m + g); without a momentum buffer
 // (beta = 0, Algorithm 2) p <- eta g.
 template <int V, bool HAS_M>
@@ -91,13 +104,291 @@ __device__ __forceinline__ Pack<V> local_update(float eta, float beta, const Pac
   return p;
 }
 
-// ------------------------------------------------------------------------------------------
-// Fused step.  For the V columns starting at `col`:
+// ==========================================================================================
+// Default kernel.  One wavefront per workgroup, which owns the pair (worker i, tile of 64 column groups = 256
+// columns) and plays two roles:
+//   A  lane l takes column group l of the tile in worker i's row, if its block was chosen by neither
+//      compressor: the purely local update  x_i -= p_i, e_i -= p_i  (28 B per element: read g, m, x, e, write
+//      m, x, e), four 128-bit loads and three 128-bit stores per lane, one contiguous KiB per stream;
+//   B  the tile's column groups are cut into slices of G = floor(64 / W) groups; this workgroup takes slices
+//      i, i + W, ... for ALL workers: lane (j, k) = (lane / G, lane % G) holds worker j's values of group
+//      slice * G + k (lanes with j >= W idle).  For groups whose block C_step chose, pbar is the in-wavefront
+//      ordered sum over j divided by W:  x_j -= pbar, e_j untouched (20 B per element).  For groups C_reset
+//      chose on a reset iteration the error reset follows at once, from registers:
+//      ebar = ordered sum of the post-step e_j / W, x_j <- (x_j - e_j) + ebar, e_j <- +0
+//      (implementation II: x_j <- ordered sum of the post-step x_j / W).
+// Every workgroup of a tile thus does its share of the tile's synchronised work whatever part of the blocks is
+// chosen, and each value is read and written exactly once.  Workgroup id -> (worker, tile) with tiles fastest:
+// the resident wavefronts sweep one worker's row through seven linear streams.
+// ==========================================================================================
+
+// Ordered worker sum inside one wavefront: every lane fetches the W values of its group k with wavefront
+// shuffles and adds them in the order j = 0, 1, ..., W-1, so all W lanes of a group end up with the same bits.
+// Must be called with all 64 lanes active.
+__device__ __forceinline__ Pack<4> worker_sum_in_wave(const Pack<4>& v, uint32_t W, uint32_t G, uint32_t k) {
+  Pack<4> sum;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) sum.v[c] = __shfl(v.v[c], static_cast<int>(k), 64);
+  for (uint32_t j = 1; j < W; ++j) {
+    const int src = static_cast<int>(j * G + k);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) sum.v[c] = sum.v[c] + __shfl(v.v[c], src, 64);
+  }
+  return sum;
+}
+
+template <bool NT, bool HAS_E, bool HAS_M>
+__global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32_t groups, uint32_t tiles) {
+  const uint32_t i = blockIdx.x / tiles, tile = blockIdx.x - i * tiles;
+  const uint32_t lane = threadIdx.x;
+  const uint32_t groups_per_block = a.block / 4u;
+  const uint32_t G = 64u / a.W;                    // column groups per slice
+  const uint32_t j = lane / G, k = lane - j * G;   // role B: worker j, group k of the slice
+  const uint32_t slices = (64u + G - 1u) / G;      // W when W divides 64, up to 2 W - 1 otherwise
+  const uint64_t tile_first = static_cast<uint64_t>(tile) * 64u;
+  const float n = static_cast<float>(a.W);
+
+  // role A
+  const uint64_t qa = tile_first + lane;
+  const bool live_a = qa < groups;
+  const uint32_t ba = static_cast<uint32_t>(live_a ? qa : 0u) / groups_per_block;
+  const bool local_a = live_a && a.mask[ba] == 0 && (a.reset_mask == nullptr || a.reset_mask[ba] == 0);
+  const uint64_t off_a = static_cast<uint64_t>(i) * a.ld + qa * 4u;
+  Pack<4> ga, ma, xa, ea;
+  if (local_a) {
+    ga = load_pack<4, NT>(a.g + off_a);
+    if constexpr (HAS_M) ma = load_pack<4, NT>(a.m + off_a);
+    xa = load_pack<4, NT>(a.x + off_a);
+    if constexpr (HAS_E) ea = load_pack<4, NT>(a.e + off_a);
+  }
+
+  for (uint32_t slice = i; slice < slices; slice += a.W) {   // runs once when W divides 64, else once or twice
+    // role B
+    const uint32_t within = slice * G + k;
+    const uint64_t qb = tile_first + within;
+    const bool live_b = j < a.W && within < 64u && qb < groups;
+    const uint32_t bb = static_cast<uint32_t>(live_b ? qb : 0u) / groups_per_block;
+    const bool step_b = live_b && a.mask[bb] != 0;
+    const bool reset_b = live_b && a.reset_mask != nullptr && a.reset_mask[bb] != 0;
+    const bool sync_b = step_b || reset_b;
+    const uint64_t off_b = static_cast<uint64_t>(j) * a.ld + qb * 4u;
+    Pack<4> gb = zero_pack<4>(), mb = zero_pack<4>(), xb = zero_pack<4>(), eb = zero_pack<4>();
+    if (sync_b) {
+      gb = load_pack<4, NT>(a.g + off_b);
+      if constexpr (HAS_M) mb = load_pack<4, NT>(a.m + off_b);
+      xb = load_pack<4, NT>(a.x + off_b);
+      if constexpr (HAS_E) {
+        if (reset_b) eb = load_pack<4, NT>(a.e + off_b);   // e is untouched by the step on a block C_step chose
+      }
+    }
+    if (slice == i && local_a) {   // role A's arithmetic, once its loads and role B's are all in flight
+      const Pack<4> p = local_update<4, HAS_M>(a.eta, a.beta, ga, ma);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        xa.v[c] = xa.v[c] - p.v[c];
+        if constexpr (HAS_E) ea.v[c] = ea.v[c] - p.v[c];
+      }
+      if constexpr (HAS_M) store_pack<4, NT>(a.m + off_a, ma);
+      store_pack<4, NT>(a.x + off_a, xa);
+      if constexpr (HAS_E) store_pack<4, NT>(a.e + off_a, ea);
+    }
+    if (__any(sync_b)) {   // wavefront-uniform: all 64 lanes take part in the shuffles below
+      Pack<4> p = zero_pack<4>();
+      if (sync_b) {
+        p = local_update<4, HAS_M>(a.eta, a.beta, gb, mb);
+        if constexpr (HAS_M) store_pack<4, NT>(a.m + off_b, mb);
+      }
+      if (__any(step_b)) {
+        const Pack<4> psum = worker_sum_in_wave(p, a.W, G, k);
+        if (step_b) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) p.v[c] = psum.v[c] / n;   // p' = pbar, r = 0
+        }
+      }
+      if (sync_b) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          xb.v[c] = xb.v[c] - p.v[c];
+          if constexpr (HAS_E) {
+            if (!step_b) eb.v[c] = eb.v[c] - p.v[c];            // r = p off the blocks C_step chose
+          }
+        }
+      }
+      if (__any(reset_b)) {
+        Pack<4> v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v.v[c] = reset_b ? (HAS_E ? eb.v[c] : xb.v[c]) : 0.0f;
+        const Pack<4> vsum = worker_sum_in_wave(v, a.W, G, k);
+        if (reset_b) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const float mean = vsum.v[c] / n;
+            if constexpr (HAS_E) {
+              xb.v[c] = (xb.v[c] - eb.v[c]) + mean;
+              eb.v[c] = 0.0f;
+            } else {
+              xb.v[c] = mean;
+            }
+          }
+        }
+      }
+      if (sync_b) {
+        store_pack<4, NT>(a.x + off_b, xb);
+        if constexpr (HAS_E) {
+          if (reset_b) store_pack<4, NT>(a.e + off_b, eb);
+        }
+      }
+    }
+  }
+}
+
+// ==========================================================================================
+// LDS-shared kernels, W <= 16.  A workgroup is W wavefronts and owns a tile of 64 column groups (256 columns) of
+// ALL workers: wavefront i works on worker i's row, lane l on column group l, so every global access of a
+// wavefront is one contiguous KiB of one row whether the block is chosen or not.
+//   block not chosen by C_step:  x_i -= p_i, e_i -= p_i, nothing is shared;
+//   block chosen by C_step:      p_i goes to LDS (W KiB per workgroup), one barrier, every lane adds the W values
+//                                of its column group in the order 0 .. W-1 and divides by W:  x_i -= pbar;
+//   block chosen by C_reset on a reset iteration: after the step's update the post-step e_i (implementation II:
+//                                x_i) is shared the same way through a second LDS area:  ebar = sum / W,
+//                                x_i <- (x_i - e_i) + ebar, e_i <- +0   (II: x_i <- xbar).
+// Block membership is decided per lane, so tiles cut by block boundaries (block < 256 columns) need no special
+// case.  The masks are the same for every wavefront of the workgroup, hence the two `any` tests below are
+// uniform over the workgroup and every wavefront reaches the same barriers.
+// ==========================================================================================
+
+// In-order sum over the workers of the values staged in LDS for this lane's column group: stage[j * 64 + lane]
+// holds worker j's four values.
+__device__ __forceinline__ Pack<4> worker_sum_from_lds(const f4* stage, uint32_t W, uint32_t lane) {
+  f4 s = stage[lane];
+  for (uint32_t j = 1; j < W; ++j) {
+    const f4 v = stage[j * 64u + lane];
+    s.x = s.x + v.x; s.y = s.y + v.y; s.z = s.z + v.z; s.w = s.w + v.w;
+  }
+  Pack<4> r;
+  r.v[0] = s.x; r.v[1] = s.y; r.v[2] = s.z; r.v[3] = s.w;
+  return r;
+}
+
+__device__ __forceinline__ f4 as_f4(const Pack<4>& p) {
+  f4 t;
+  t.x = p.v[0]; t.y = p.v[1]; t.z = p.v[2]; t.w = p.v[3];
+  return t;
+}
+
+template <bool NT, bool HAS_E, bool HAS_M>
+__global__ __launch_bounds__(1024) void cser_step_shared_kernel(StepParams a, uint32_t groups) {
+  extern __shared__ f4 stage[];
+  const uint32_t lane = threadIdx.x & 63u, i = threadIdx.x >> 6;
+  const uint64_t q = static_cast<uint64_t>(blockIdx.x) * 64u + lane;
+  const bool live = q < groups;
+  const uint32_t b = static_cast<uint32_t>(live ? q : 0u) / (a.block / 4u);
+  const bool step_c = live && a.mask[b] != 0;
+  const bool reset_c = live && a.reset_mask != nullptr && a.reset_mask[b] != 0;
+  const bool touches_e = HAS_E && live && (!step_c || reset_c);   // e is untouched by the step on a block C_step chose
+  const uint64_t off = static_cast<uint64_t>(i) * a.ld + q * 4u;
+  Pack<4> g = zero_pack<4>(), m = zero_pack<4>(), x = zero_pack<4>(), e = zero_pack<4>();
+  if (live) {
+    g = load_pack<4, NT>(a.g + off);
+    if constexpr (HAS_M) m = load_pack<4, NT>(a.m + off);
+    x = load_pack<4, NT>(a.x + off);
+  }
+  if (touches_e) e = load_pack<4, NT>(a.e + off);
+  Pack<4> p = local_update<4, HAS_M>(a.eta, a.beta, g, m);
+  if constexpr (HAS_M) {
+    if (live) store_pack<4, NT>(a.m + off, m);
+  }
+  const float n = static_cast<float>(a.W);
+  if (__any(step_c)) {
+    if (step_c) stage[i * 64u + lane] = as_f4(p);
+    __syncthreads();
+    if (step_c) {
+      const Pack<4> psum = worker_sum_from_lds(stage, a.W, lane);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) p.v[c] = psum.v[c] / n;      // p' = pbar, r = 0
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    x.v[c] = x.v[c] - p.v[c];
+    if constexpr (HAS_E) {
+      if (!step_c) e.v[c] = e.v[c] - p.v[c];                    // r = p off the blocks C_step chose
+    }
+  }
+  if (a.reset_mask != nullptr && __any(reset_c)) {
+    f4* stage2 = stage + a.W * 64u;
+    if (reset_c) stage2[i * 64u + lane] = as_f4(HAS_E ? e : x);
+    __syncthreads();
+    if (reset_c) {
+      const Pack<4> vsum = worker_sum_from_lds(stage2, a.W, lane);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float mean = vsum.v[c] / n;
+        if constexpr (HAS_E) {
+          x.v[c] = (x.v[c] - e.v[c]) + mean;
+          e.v[c] = 0.0f;
+        } else {
+          x.v[c] = mean;
+        }
+      }
+    }
+  }
+  if (live) store_pack<4, NT>(a.x + off, x);
+  if (touches_e) store_pack<4, NT>(a.e + off, e);
+}
+
+// Error reset on its own (cser_error_reset), same shape: a workgroup of W wavefronts owns 64 column groups of
+// the blocks listed in idx, wavefront i reads worker i's e and x once (one contiguous KiB each when the block has
+// at least 256 columns), the worker sum goes through LDS, and x and e are written once:
+//   ebar = (e_0 + e_1 + ... + e_{W-1}) / W ;  x_i <- (x_i - e_i) + ebar ;  e_i <- +0
+// (implementation II, no e:  x_i <- (x_0 + ... + x_{W-1}) / W).  idx is in increasing order, so consecutive
+// workgroups sweep the rows forwards (a list in draw order costs 20 % of the bandwidth).
+template <bool NT, bool HAS_E>
+__global__ __launch_bounds__(1024) void cser_reset_shared_kernel(ResetParams a, uint32_t groups_per_block,
+                                                                  uint64_t total_groups) {
+  extern __shared__ f4 stage[];
+  const uint32_t lane = threadIdx.x & 63u, i = threadIdx.x >> 6;
+  const uint64_t q = static_cast<uint64_t>(blockIdx.x) * 64u + lane;
+  bool live = q < total_groups;
+  const uint32_t j = static_cast<uint32_t>((live ? q : 0u) / groups_per_block);
+  const uint32_t within = static_cast<uint32_t>((live ? q : 0u) - static_cast<uint64_t>(j) * groups_per_block);
+  const uint64_t col = static_cast<uint64_t>(a.idx[j]) * a.block + static_cast<uint64_t>(within) * 4u;
+  live = live && col + 4u <= a.d;   // ragged last block; a trailing partial group goes to the element-wise kernel
+  const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
+  Pack<4> x = zero_pack<4>(), e = zero_pack<4>();
+  if (live) {
+    if constexpr (HAS_E) e = load_pack<4, NT>(a.e + off);
+    x = load_pack<4, NT>(a.x + off);
+  }
+  stage[i * 64u + lane] = as_f4(HAS_E ? e : x);
+  __syncthreads();
+  if (live) {
+    const Pack<4> vsum = worker_sum_from_lds(stage, a.W, lane);
+    const float n = static_cast<float>(a.W);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float mean = vsum.v[c] / n;
+      if constexpr (HAS_E) {
+        x.v[c] = (x.v[c] - e.v[c]) + mean;
+        e.v[c] = 0.0f;
+      } else {
+        x.v[c] = mean;
+      }
+    }
+    store_pack<4, NT>(a.x + off, x);
+    if constexpr (HAS_E) store_pack<4, NT>(a.e + off, e);
+  }
+}
+
+// ==========================================================================================
+// General kernels: one lane per group of V columns walks the worker axis itself (a private chain of adds in
+// registers).  Any W, any block size (V = 1 when block is not a multiple of 4 columns, and for the up to 3
+// trailing columns of a d that is not).  U workers are processed per batch: all their loads are issued before
+// any arithmetic.
 //   block not chosen by C_step:  C(p_i) = 0 on every worker, so the mean is 0, p'_i = r_i = p_i:
-//                                x_i -= p_i, e_i -= p_i                       (28 B per element)
-//   block chosen:                r_i = 0, p'_i = mean_j p_j:  x_i -= pbar, e_i untouched (20 B)
-// U workers are processed per batch: all their loads are issued before any arithmetic.
-// ------------------------------------------------------------------------------------------
+//                                x_i -= p_i, e_i -= p_i
+//   block chosen:                r_i = 0, p'_i = mean_j p_j:  x_i -= pbar, e_i untouched
+// ==========================================================================================
 template <int V, int U, bool NT, bool HAS_E, bool HAS_M>
 __device__ __forceinline__ void step_local_batch(const StepParams& a, uint64_t col, uint32_t i0) {
   Pack<V> g[U], m[U], x[U], e[U];
@@ -139,7 +430,7 @@ __device__ __forceinline__ void step_sum_batch(const StepParams& a, uint64_t col
     const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g[u], m[u]);
     if constexpr (HAS_M) store_pack<V, NT>(a.m + off, m[u]);
 #pragma unroll
-    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + p.v[c];   // workers in order i = 0, 1, ...
+    for (int c = 0; c < V; ++c) sum.v[c] = (i0 + u == 0u) ? p.v[c] : sum.v[c] + p.v[c];   // workers in order 0, 1, ...
   }
 }
 
@@ -164,9 +455,7 @@ __device__ __forceinline__ void step_columns(const StepParams& a, uint64_t col, 
     for (; i + U <= a.W; i += U) step_local_batch<V, U, NT, HAS_E, HAS_M>(a, col, i);
     for (; i < a.W; ++i) step_local_batch<V, 1, NT, HAS_E, HAS_M>(a, col, i);
   } else {
-    Pack<V> sum;
-#pragma unroll
-    for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
+    Pack<V> sum = zero_pack<V>();
     uint32_t i = 0;
     for (; i + U <= a.W; i += U) step_sum_batch<V, U, NT, HAS_M>(a, col, i, sum);
     for (; i < a.W; ++i) step_sum_batch<V, 1, NT, HAS_M>(a, col, i, sum);
@@ -180,65 +469,19 @@ __device__ __forceinline__ void step_columns(const StepParams& a, uint64_t col, 
   }
 }
 
-// Chosen block, W <= 8: the same arithmetic as the chosen branch of step_columns, but g, m and x of all
-// workers are requested in one go and held in registers, so the lane waits for memory once
-// instead of four times (loads of absent workers i >= W are skipped, their slots unused).
-template <int V, bool NT, bool HAS_M>
-__device__ __forceinline__ void step_chosen_up_to_8(const StepParams& a, uint64_t col) {
-  Pack<V> g[8], m[8], x[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (static_cast<uint32_t>(i) < a.W) {
-      const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
-      g[i] = load_pack<V, NT>(a.g + off);
-      if constexpr (HAS_M) m[i] = load_pack<V, NT>(a.m + off);
-      x[i] = load_pack<V, NT>(a.x + off);
-    }
-  }
-  Pack<V> sum;
-#pragma unroll
-  for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (static_cast<uint32_t>(i) < a.W) {
-      const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g[i], m[i]);
-      if constexpr (HAS_M) store_pack<V, NT>(a.m + static_cast<uint64_t>(i) * a.ld + col, m[i]);
-#pragma unroll
-      for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + p.v[c];   // workers in order i = 0, 1, ...
-    }
-  }
-  const float n = static_cast<float>(a.W);
-  Pack<V> pbar;
-#pragma unroll
-  for (int c = 0; c < V; ++c) pbar.v[c] = sum.v[c] / n;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (static_cast<uint32_t>(i) < a.W) {
-#pragma unroll
-      for (int c = 0; c < V; ++c) x[i].v[c] = x[i].v[c] - pbar.v[c];
-      store_pack<V, NT>(a.x + static_cast<uint64_t>(i) * a.ld + col, x[i]);
-    }
-  }
-}
-
 // Reset iterations (t mod H = 0) with the reset fused into the step: the V columns at `col` belong
 // to a block C_reset chose, so after the step's own update the error reset follows at once,
 //   ebar = (e'_0 + ... + e'_{W-1}) / W ;  x_i <- (x'_i - e'_i) + ebar ;  e_i <- +0
 // (implementation II: x_i <- (x'_0 + ... + x'_{W-1}) / W), where x', e' are the values after the
-// step.  Every operation and its order are those of running the step kernel and then the reset
-// kernel; x and e just travel through registers instead of memory.  A worker's update p_i is
-// recomputed from g_i and the old m_i in each pass (m is stored only in the last), so no pass reads
-// what an earlier pass wrote.  Plain (temporal) accesses: the re-reads are meant to hit in L2.
+// step.  Every operation and its order are those of running the step and then the reset; x and e just travel
+// through registers instead of memory.  A worker's update p_i is recomputed from g_i and the old m_i in each
+// pass (m is stored only in the last), so no pass reads what an earlier pass wrote.  Plain (temporal) accesses:
+// the re-reads are meant to hit in L2.
 template <int V, bool HAS_E, bool HAS_M>
 __device__ __forceinline__ void step_and_reset_columns(const StepParams& a, uint64_t col, bool step_chosen) {
   const float n = static_cast<float>(a.W);
-  Pack<V> pbar, sum, mean, zero;
-#pragma unroll
-  for (int c = 0; c < V; ++c) {
-    pbar.v[c] = 0.0f;
-    sum.v[c] = 0.0f;
-    zero.v[c] = 0.0f;
-  }
+  const Pack<V> zero = zero_pack<V>();
+  Pack<V> pbar = zero, sum = zero, mean;
   if (step_chosen) {   // pbar = mean_i p_i
     Pack<V> psum = zero;
     for (uint32_t i = 0; i < a.W; ++i) {
@@ -248,7 +491,7 @@ __device__ __forceinline__ void step_and_reset_columns(const StepParams& a, uint
       if constexpr (HAS_M) m = load_pack<V, false>(a.m + off);
       const Pack<V> p = local_update<V, HAS_M>(a.eta, a.beta, g, m);
 #pragma unroll
-      for (int c = 0; c < V; ++c) psum.v[c] = psum.v[c] + p.v[c];
+      for (int c = 0; c < V; ++c) psum.v[c] = i == 0u ? p.v[c] : psum.v[c] + p.v[c];
     }
 #pragma unroll
     for (int c = 0; c < V; ++c) pbar.v[c] = psum.v[c] / n;
@@ -269,7 +512,7 @@ __device__ __forceinline__ void step_and_reset_columns(const StepParams& a, uint
       for (int c = 0; c < V; ++c) v.v[c] = v.v[c] - pbar.v[c];     // x - pbar (e is untouched on chosen blocks)
     }
 #pragma unroll
-    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + v.v[c];
+    for (int c = 0; c < V; ++c) sum.v[c] = i == 0u ? v.v[c] : sum.v[c] + v.v[c];
   }
 #pragma unroll
   for (int c = 0; c < V; ++c) mean.v[c] = sum.v[c] / n;
@@ -298,277 +541,37 @@ __device__ __forceinline__ void step_and_reset_columns(const StepParams& a, uint
   }
 }
 
-// Columns [col_begin, col_end) in groups of V; group q covers col_begin + q*V ...  `groups` is
-// the number of whole groups.  groups_per_block = block / V (vector path: block % 4 == 0 and
-// col_begin % block == 0, so a group never straddles two blocks).
-template <int V, int U, bool NT, bool HAS_E, bool HAS_M>
-__global__ __launch_bounds__(1024) void cser_step_kernel(StepParams a, uint64_t col_begin, uint32_t groups) {
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-  for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; q < groups; q += stride) {
-    const uint64_t col = col_begin + q * V;
-    uint32_t b;
-    if constexpr (V == 4) b = static_cast<uint32_t>(q) / (a.block / 4u);   // vector path starts at column 0
-    else b = static_cast<uint32_t>(col / a.block);
-    const bool step_chosen = a.mask[b] != 0;
-    if (a.reset_mask != nullptr && a.reset_mask[b] != 0) step_and_reset_columns<V, HAS_E, HAS_M>(a, col, step_chosen);
-    else step_columns<V, U, NT, HAS_E, HAS_M>(a, col, step_chosen);
-  }
+// Columns [col_begin, col_begin + groups * V) in groups of V.  With V = 4, col_begin is 0 and block is a
+// multiple of 4, so a group never straddles two blocks.
+template <int V, bool NT, bool HAS_E, bool HAS_M>
+__global__ __launch_bounds__(256) void cser_step_general_kernel(StepParams a, uint64_t col_begin, uint32_t groups) {
+  const uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (q >= groups) return;
+  const uint64_t col = col_begin + q * V;
+  uint32_t b;
+  if constexpr (V == 4) b = static_cast<uint32_t>(q) / (a.block / 4u);
+  else b = static_cast<uint32_t>(col / a.block);
+  const bool step_chosen = a.mask[b] != 0;
+  if (a.reset_mask != nullptr && a.reset_mask[b] != 0) step_and_reset_columns<V, HAS_E, HAS_M>(a, col, step_chosen);
+  else step_columns<V, 4, NT, HAS_E, HAS_M>(a, col, step_chosen);
 }
 
-// Row-split variant of the vector path.  A workgroup owns one worker's row over a tile of
-// C * blockDim.x column groups (each lane takes C groups spaced blockDim.x apart, so every access
-// stays coalesced): unchosen blocks need nothing from the other workers.  Chosen blocks need the
-// worker mean (and so do the blocks C_reset chose, on a reset iteration with the reset fused in);
-// the workgroup of worker 0 walks all rows for those.
-// `order` maps the workgroup id to its (worker, tile) pair:
-//   0  tiles fastest: consecutive workgroups sweep one worker's row, then the next worker's
-//   1  workers fastest: consecutive workgroups take the same tile of every worker
-//   2  as 0, but the ids are first regrouped so that each of the 8 XCDs (ids are dealt to them
-//      round-robin) sweeps one contiguous eighth of the (worker, tile) sequence
-// NTMODE: bit 0 = non-temporal loads, bit 1 = non-temporal stores.
-template <int C, int NTMODE, bool HAS_E, bool HAS_M>
-__global__ __launch_bounds__(1024) void cser_step_rows_kernel(StepParams a, uint32_t groups, uint32_t tiles,
-                                                               uint32_t order) {
-  constexpr bool NTL = (NTMODE & 1) != 0, NTS = (NTMODE & 2) != 0;
-  uint32_t tile, i;
-  if (order == 1) {
-    tile = blockIdx.x / a.W;
-    i = blockIdx.x - tile * a.W;
-  } else {
-    uint32_t linear = blockIdx.x;
-    if (order == 2) {
-      const uint32_t per_xcd = gridDim.x / 8u;   // the launcher rounds the grid up to a multiple of 8
-      linear = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-      if (linear >= tiles * a.W) return;
-    }
-    i = linear / tiles;
-    tile = linear - i * tiles;
-  }
-  const uint64_t row = static_cast<uint64_t>(i) * a.ld;
-  const uint32_t groups_per_block = a.block / 4u;
-  uint32_t q[C];
-  bool local[C], chosen[C], reset_chosen[C];
-  Pack<4> g[C], m[C], x[C], e[C];
-#pragma unroll
-  for (int c = 0; c < C; ++c) {
-    const uint64_t q64 = (static_cast<uint64_t>(tile) * C + c) * blockDim.x + threadIdx.x;
-    const bool live = q64 < groups;
-    q[c] = live ? static_cast<uint32_t>(q64) : 0u;
-    const uint32_t b = q[c] / groups_per_block;
-    chosen[c] = live && a.mask[b] != 0;
-    reset_chosen[c] = live && a.reset_mask != nullptr && a.reset_mask[b] != 0;
-    local[c] = live && !chosen[c] && !reset_chosen[c];
-    if (local[c]) {
-      const uint64_t off = row + static_cast<uint64_t>(q[c]) * 4;
-      g[c] = load_pack<4, NTL>(a.g + off);
-      if constexpr (HAS_M) m[c] = load_pack<4, NTL>(a.m + off);
-      x[c] = load_pack<4, NTL>(a.x + off);
-      if constexpr (HAS_E) e[c] = load_pack<4, NTL>(a.e + off);
-    }
-  }
-#pragma unroll
-  for (int c = 0; c < C; ++c) {
-    if (local[c]) {
-      const uint64_t off = row + static_cast<uint64_t>(q[c]) * 4;
-      const Pack<4> p = local_update<4, HAS_M>(a.eta, a.beta, g[c], m[c]);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        x[c].v[k] = x[c].v[k] - p.v[k];
-        if constexpr (HAS_E) e[c].v[k] = e[c].v[k] - p.v[k];
-      }
-      if constexpr (HAS_M) store_pack<4, NTS>(a.m + off, m[c]);
-      store_pack<4, NTS>(a.x + off, x[c]);
-      if constexpr (HAS_E) store_pack<4, NTS>(a.e + off, e[c]);
-    }
-  }
-  if (i == 0) {
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-      const uint64_t col = static_cast<uint64_t>(q[c]) * 4;
-      if (reset_chosen[c]) step_and_reset_columns<4, HAS_E, HAS_M>(a, col, chosen[c]);
-      else if (chosen[c]) {
-        if (a.W <= 8) step_chosen_up_to_8<4, NTL && NTS, HAS_M>(a, col);
-        else step_columns<4, 4, NTL && NTS, HAS_E, HAS_M>(a, col, true);
-      }
-    }
-  }
-}
-
-// Ordered worker sum inside one wavefront.  Lanes are laid out as (worker j, group k) = (lane / G,
-// lane % G); every lane fetches the W values of its group k with wavefront shuffles and adds them in
-// the order j = 0, 1, ..., W-1 -- the order of a sequential evaluation -- so all W lanes of a group
-// end up with the same bits.  Must be called with all 64 lanes active.
-template <int V>
-__device__ __forceinline__ Pack<V> worker_sum_in_wave(const Pack<V>& v, uint32_t W, uint32_t G, uint32_t k) {
-  Pack<V> sum;
-#pragma unroll
-  for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
-  for (uint32_t j = 0; j < W; ++j) {
-    const int src = static_cast<int>(j * G + k);
-#pragma unroll
-    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + __shfl(v.v[c], src, 64);
-  }
-  return sum;
-}
-
-// Balanced row-split kernel for W a power of two up to 64; one wavefront per workgroup, which owns
-// the pair (worker i, tile of 64 column groups = 256 columns) and plays two roles:
-//   A  lane l takes column group l of the tile in worker i's row, if its block was chosen by neither
-//      compressor: the purely local update, as in cser_step_rows_kernel;
-//   B  the tile's column groups are cut into W slices of G = 64 / W groups; this workgroup takes
-//      slice i for ALL workers: lane (j, k) holds worker j's values of group i*G + k.  For groups
-//      whose block C_step chose, pbar is the in-wavefront ordered sum over j divided by W; for groups
-//      C_reset chose on a reset iteration the error reset follows at once, from registers:
-//      ebar = ordered sum of the post-step e_j / W, x_j <- (x_j - e_j) + ebar, e_j <- +0
-//      (implementation II: x_j <- ordered sum of the post-step x_j / W).
-// Every workgroup of a tile thus does 1/W of the tile's synchronised work, whatever share of the
-// blocks is chosen, and each value is read and written exactly once.  The arithmetic and its order
-// are those of the other kernels.
-template <int NTMODE, bool HAS_E, bool HAS_M>
-__global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32_t groups, uint32_t tiles,
-                                                             uint32_t order, uint32_t log2_w) {
-  constexpr bool NTL = (NTMODE & 1) != 0, NTS = (NTMODE & 2) != 0;
-  uint32_t tile, i;
-  if (order == 1) {
-    tile = blockIdx.x >> log2_w;
-    i = blockIdx.x & (a.W - 1u);
-  } else {
-    uint32_t linear = blockIdx.x;
-    if (order == 2) {
-      const uint32_t per_xcd = gridDim.x / 8u;   // the launcher rounds the grid up to a multiple of 8
-      linear = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-      if (linear >= tiles * a.W) return;         // uniform over the workgroup
-    }
-    i = linear / tiles;
-    tile = linear - i * tiles;
-  }
-  const uint32_t lane = threadIdx.x;
-  const uint32_t groups_per_block = a.block / 4u;
-  const uint32_t G = 64u >> log2_w;              // column groups per slice
-  const uint32_t j = lane / G, k = lane - j * G; // role B: worker j, group k of slice i
-  const uint64_t tile_first = static_cast<uint64_t>(tile) * 64u;
-
-  // role A
-  const uint64_t qa = tile_first + lane;
-  const bool live_a = qa < groups;
-  const uint32_t ba = static_cast<uint32_t>(live_a ? qa : 0u) / groups_per_block;
-  const bool local_a = live_a && a.mask[ba] == 0 && (a.reset_mask == nullptr || a.reset_mask[ba] == 0);
-  // role B
-  const uint64_t qb = tile_first + static_cast<uint64_t>(i) * G + k;
-  const bool live_b = qb < groups;
-  const uint32_t bb = static_cast<uint32_t>(live_b ? qb : 0u) / groups_per_block;
-  const bool step_b = live_b && a.mask[bb] != 0;
-  const bool reset_b = live_b && a.reset_mask != nullptr && a.reset_mask[bb] != 0;
-  const bool sync_b = step_b || reset_b;
-
-  const uint64_t off_a = static_cast<uint64_t>(i) * a.ld + qa * 4u;
-  const uint64_t off_b = static_cast<uint64_t>(j) * a.ld + qb * 4u;
-  Pack<4> ga, ma, xa, ea, gb, mb, xb, eb;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    gb.v[c] = 0.0f; mb.v[c] = 0.0f; xb.v[c] = 0.0f; eb.v[c] = 0.0f;
-  }
-  if (local_a) {
-    ga = load_pack<4, NTL>(a.g + off_a);
-    if constexpr (HAS_M) ma = load_pack<4, NTL>(a.m + off_a);
-    xa = load_pack<4, NTL>(a.x + off_a);
-    if constexpr (HAS_E) ea = load_pack<4, NTL>(a.e + off_a);
-  }
-  if (sync_b) {
-    gb = load_pack<4, NTL>(a.g + off_b);
-    if constexpr (HAS_M) mb = load_pack<4, NTL>(a.m + off_b);
-    xb = load_pack<4, NTL>(a.x + off_b);
-    if constexpr (HAS_E) {
-      if (reset_b) eb = load_pack<4, NTL>(a.e + off_b);   // e is untouched by the step on a block C_step chose
-    }
-  }
-  if (local_a) {
-    const Pack<4> p = local_update<4, HAS_M>(a.eta, a.beta, ga, ma);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      xa.v[c] = xa.v[c] - p.v[c];
-      if constexpr (HAS_E) ea.v[c] = ea.v[c] - p.v[c];
-    }
-    if constexpr (HAS_M) store_pack<4, NTS>(a.m + off_a, ma);
-    store_pack<4, NTS>(a.x + off_a, xa);
-    if constexpr (HAS_E) store_pack<4, NTS>(a.e + off_a, ea);
-  }
-  if (__any(sync_b)) {   // wavefront-uniform: all 64 lanes take part in the shuffles below
-    Pack<4> p;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) p.v[c] = 0.0f;
-    if (sync_b) {
-      p = local_update<4, HAS_M>(a.eta, a.beta, gb, mb);
-      if constexpr (HAS_M) store_pack<4, NTS>(a.m + off_b, mb);
-    }
-    const float n = static_cast<float>(a.W);
-    if (__any(step_b)) {
-      const Pack<4> psum = worker_sum_in_wave<4>(p, a.W, G, k);
-      if (step_b) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) p.v[c] = psum.v[c] / n;   // p' = pbar, r = 0
-      }
-    }
-    if (sync_b) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        xb.v[c] = xb.v[c] - p.v[c];
-        if constexpr (HAS_E) {
-          if (!step_b) eb.v[c] = eb.v[c] - p.v[c];            // r = p off the blocks C_step chose
-        }
-      }
-    }
-    if (__any(reset_b)) {
-      Pack<4> v;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) v.v[c] = reset_b ? (HAS_E ? eb.v[c] : xb.v[c]) : 0.0f;
-      const Pack<4> vsum = worker_sum_in_wave<4>(v, a.W, G, k);
-      if (reset_b) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const float mean = vsum.v[c] / n;
-          if constexpr (HAS_E) {
-            xb.v[c] = (xb.v[c] - eb.v[c]) + mean;
-            eb.v[c] = 0.0f;
-          } else {
-            xb.v[c] = mean;
-          }
-        }
-      }
-    }
-    if (sync_b) {
-      store_pack<4, NTS>(a.x + off_b, xb);
-      if constexpr (HAS_E) {
-        if (reset_b) store_pack<4, NTS>(a.e + off_b, eb);
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// Error reset (Algorithm 3, t mod H = 0) on the V columns at `col` of a chosen block:
-//   ebar = (e_0 + e_1 + ... + e_{W-1}) / W ;  x_i <- (x_i - e_i) + ebar ;  e_i <- +0
-// Implementation II (no e): x_i <- (x_0 + ... + x_{W-1}) / W.
-// The second pass re-reads e_i; the lines were just fetched by this lane, so they come from L2.
-// ------------------------------------------------------------------------------------------
+// Error reset on the V columns at `col` of a chosen block; the second pass re-reads e_i (the lines were just
+// fetched by this lane, so they come from L2).
 template <int V, bool HAS_E>
 __device__ __forceinline__ void reset_columns(const ResetParams& a, uint64_t col) {
   float* src = HAS_E ? a.e : a.x;
-  Pack<V> sum;
-#pragma unroll
-  for (int c = 0; c < V; ++c) sum.v[c] = 0.0f;
+  Pack<V> sum = zero_pack<V>();
   for (uint32_t i = 0; i < a.W; ++i) {
     const Pack<V> v = load_pack<V, false>(src + static_cast<uint64_t>(i) * a.ld + col);
 #pragma unroll
-    for (int c = 0; c < V; ++c) sum.v[c] = sum.v[c] + v.v[c];
+    for (int c = 0; c < V; ++c) sum.v[c] = i == 0u ? v.v[c] : sum.v[c] + v.v[c];
   }
   const float n = static_cast<float>(a.W);
-  Pack<V> mean, zero;
+  const Pack<V> zero = zero_pack<V>();
+  Pack<V> mean;
 #pragma unroll
-  for (int c = 0; c < V; ++c) {
-    mean.v[c] = sum.v[c] / n;
-    zero.v[c] = 0.0f;
-  }
+  for (int c = 0; c < V; ++c) mean.v[c] = sum.v[c] / n;
   for (uint32_t i = 0; i < a.W; ++i) {
     const uint64_t off = static_cast<uint64_t>(i) * a.ld + col;
     if constexpr (HAS_E) {
@@ -584,30 +587,27 @@ __device__ __forceinline__ void reset_columns(const ResetParams& a, uint64_t col
   }
 }
 
-// Vector path: one lane per 4-column group of a chosen block; the block list comes from idx.
-template <bool HAS_E>
-__global__ __launch_bounds__(256) void cser_reset_kernel(ResetParams a, uint32_t groups_per_block,
-                                                          uint64_t total_groups) {
+// V = 4: one lane per 4-column group of a listed block.  V = 1: one lane per column of [col_begin, col_begin +
+// total), chosen or not by the mask (any alignment, any block size).
+template <int V, bool HAS_E>
+__global__ __launch_bounds__(256) void cser_reset_general_kernel(ResetParams a, const uint8_t* mask, uint32_t groups_per_block,
+                                                                  uint64_t total, uint64_t col_begin) {
   const uint64_t q = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (q >= total_groups) return;
-  const uint32_t j = static_cast<uint32_t>(q / groups_per_block);
-  const uint32_t within = static_cast<uint32_t>(q - static_cast<uint64_t>(j) * groups_per_block);
-  const uint64_t col = static_cast<uint64_t>(a.idx[j]) * a.block + static_cast<uint64_t>(within) * 4;
-  if (col + 4 > a.d) return;   // ragged last block; a trailing partial group goes to the scalar kernel
-  reset_columns<4, HAS_E>(a, col);
+  if (q >= total) return;
+  if constexpr (V == 4) {
+    const uint32_t j = static_cast<uint32_t>(q / groups_per_block);
+    const uint32_t within = static_cast<uint32_t>(q - static_cast<uint64_t>(j) * groups_per_block);
+    const uint64_t col = static_cast<uint64_t>(a.idx[j]) * a.block + static_cast<uint64_t>(within) * 4u;
+    if (col + 4u > a.d) return;   // ragged last block; a trailing partial group goes to the V = 1 launch
+    reset_columns<4, HAS_E>(a, col);
+  } else {
+    const uint64_t col = col_begin + q;
+    if (mask[col / a.block] == 0) return;
+    reset_columns<1, HAS_E>(a, col);
+  }
 }
 
-// Element-wise path over columns [col_begin, col_end): uses the mask, any alignment.
-template <bool HAS_E>
-__global__ __launch_bounds__(256) void cser_reset_scalar_kernel(ResetParams a, const uint8_t* mask,
-                                                                 uint64_t col_begin, uint64_t col_end) {
-  const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (col >= col_end) return;
-  if (mask[col / a.block] == 0) return;
-  reset_columns<1, HAS_E>(a, col);
-}
-
-// ------------------------------------------------------------------------------------------
+// ==========================================================================================
 // Block selector.  All workers must pick the same k of the B blocks from a shared seed
 // (Definition 2).  The choice is {pi(0), ..., pi(k-1)} for a keyed permutation pi of [0, B):
 // block b is chosen iff pi^-1(b) < k, which every block can decide for itself -- no sort, no
@@ -616,8 +616,8 @@ __global__ __launch_bounds__(256) void cser_reset_scalar_kernel(ResetParams a, c
 // pi: 8-round balanced Feistel network on 2h bits (2^(2h) >= B), round function = low h bits of
 // word 0 of Philox-4x32-10 (Salmon et al., SC'11) keyed by the seed with counter
 // (half, stream*65536 + round, t_lo, t_hi); values >= B are walked through the network again
-// (cycle walking).  This kernel evaluates the inverse.
-// ------------------------------------------------------------------------------------------
+// (cycle walking).
+// ==========================================================================================
 __device__ __forceinline__ uint32_t philox_first_word(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                       uint32_t k0, uint32_t k1) {
   constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;
@@ -636,9 +636,9 @@ __device__ __forceinline__ uint32_t philox_first_word(uint32_t c0, uint32_t c1, 
   return c0;
 }
 
-// blockIdx.y selects the iteration t0 + blockIdx.y * t_stride (the choice is a pure function of t, so several
-// iterations can be drawn ahead in one launch); its mask goes to mask + blockIdx.y * B.  idx may be
-// null; when given it is only meaningful for a launch with gridDim.y == 1.
+// Inverse form.  blockIdx.y selects the iteration t0 + blockIdx.y * t_stride (the choice is a pure function of
+// t, so several iterations can be drawn ahead in one launch); its mask goes to mask + blockIdx.y * B.  idx may
+// be null; when given it is only meaningful for a launch with gridDim.y == 1.
 __global__ __launch_bounds__(256) void grbs_select_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
                                                            uint64_t t0, uint64_t t_stride, uint32_t B, uint32_t k,
                                                            uint32_t half_bits, uint8_t* mask, uint32_t* idx) {
@@ -708,9 +708,35 @@ __global__ __launch_bounds__(256) void grbs_scatter_kernel(uint32_t seed_lo, uin
   }
 }
 
+// The block ids b with mask[b] != 0 in increasing order, out[0 .. k).  One workgroup of 1024 lanes: each lane
+// counts the chosen blocks of its contiguous share of the mask, an inclusive scan over the 1024 counts gives
+// every lane the position of its first entry, and a second walk over the share writes the ids.  `k` bounds the
+// writes (the mask holds exactly k chosen blocks by construction).
+__global__ __launch_bounds__(1024) void ordered_list_kernel(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* out) {
+  __shared__ uint32_t counts[1024];
+  const uint32_t tid = threadIdx.x;
+  const uint64_t per = (static_cast<uint64_t>(B) + 1023u) / 1024u;
+  const uint64_t b0 = tid * per < B ? tid * per : B;
+  const uint64_t b1 = b0 + per < B ? b0 + per : B;
+  uint32_t c = 0;
+  for (uint64_t b = b0; b < b1; ++b) c += mask[b] != 0 ? 1u : 0u;
+  counts[tid] = c;
+  __syncthreads();
+  for (uint32_t step = 1; step < 1024u; step <<= 1) {
+    const uint32_t add = tid >= step ? counts[tid - step] : 0u;
+    __syncthreads();
+    counts[tid] += add;
+    __syncthreads();
+  }
+  uint32_t pos = counts[tid] - c;
+  for (uint64_t b = b0; b < b1; ++b) {
+    if (mask[b] != 0 && pos < k) out[pos++] = static_cast<uint32_t>(b);
+  }
+}
+
 __global__ __launch_bounds__(256) void fill_bytes_kernel(uint8_t* p, uint64_t n, uint8_t value) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-  const uint64_t n4 = n / 4;   // p comes from hipMalloc: 4-byte aligned
+  const uint64_t n4 = n / 4;   // p is at least 4-byte aligned
   uint32_t* p4 = reinterpret_cast<uint32_t*>(p);
   const uint32_t word = value * 0x01010101u;
   for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n4; i += stride) p4[i] = word;
@@ -735,137 +761,125 @@ uint32_t half_bits_for(uint32_t B) {
   return (bits + 1) / 2;
 }
 
-template <int V, int U, bool NT>
-hipError_t launch_step_flags(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, uint32_t threads,
-                             hipStream_t s) {
-  const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
-  if (has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, true>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
-  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, true, false>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
-  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, true>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
-  else hipLaunchKernelGGL((cser_step_kernel<V, U, NT, false, false>), dim3(grid), dim3(threads), 0, s, p, col_begin, groups);
-  return hipGetLastError();
-}
-
-template <int V, bool NT>
-hipError_t launch_step_batch(const StepParams& p, uint64_t col_begin, uint32_t groups, uint32_t grid, uint32_t threads,
-                             int batch, hipStream_t s) {
-  switch (batch) {
-    case 1: return launch_step_flags<V, 1, NT>(p, col_begin, groups, grid, threads, s);
-    case 2: return launch_step_flags<V, 2, NT>(p, col_begin, groups, grid, threads, s);
-    case 8: return launch_step_flags<V, 8, NT>(p, col_begin, groups, grid, threads, s);
-    default: return launch_step_flags<V, 4, NT>(p, col_begin, groups, grid, threads, s);
-  }
+// Calls f(NT, HAS_E, HAS_M) with the three flags as compile-time constants.
+template <class F>
+auto with_flags(bool nt, bool has_e, bool has_m, F&& f) {
+  auto pick_m = [&](auto NT, auto E) { return has_m ? f(NT, E, std::true_type{}) : f(NT, E, std::false_type{}); };
+  auto pick_e = [&](auto NT) { return has_e ? pick_m(NT, std::true_type{}) : pick_m(NT, std::false_type{}); };
+  return nt ? pick_e(std::true_type{}) : pick_e(std::false_type{});
 }
 
 template <int V>
-hipError_t launch_step_range(const StepParams& p, uint64_t col_begin, uint64_t col_end, const Tuning& tune,
-                             hipStream_t s) {
+hipError_t launch_general(const StepParams& p, uint64_t col_begin, uint64_t col_end, bool nt, hipStream_t s) {
   if (col_end <= col_begin) return hipSuccess;
   const uint64_t groups64 = (col_end - col_begin) / V;
   if (groups64 == 0) return hipSuccess;
   const uint32_t groups = static_cast<uint32_t>(groups64);
-  const uint32_t threads = static_cast<uint32_t>(tune.threads);
-  uint64_t grid = (groups64 + threads - 1) / threads;
-  if (tune.wg_cap > 0 && grid > static_cast<uint64_t>(tune.wg_cap)) grid = static_cast<uint64_t>(tune.wg_cap);
-  if (tune.nontemporal) return launch_step_batch<V, true>(p, col_begin, groups, static_cast<uint32_t>(grid), threads, tune.batch, s);
-  return launch_step_batch<V, false>(p, col_begin, groups, static_cast<uint32_t>(grid), threads, tune.batch, s);
+  const dim3 grid(static_cast<uint32_t>((groups64 + 255) / 256)), block(256);
+  return with_flags(nt, p.e != nullptr, p.m != nullptr, [&](auto NT, auto E, auto M) {
+    hipLaunchKernelGGL((cser_step_general_kernel<V, decltype(NT)::value, decltype(E)::value, decltype(M)::value>), grid, block,
+                       0, s, p, col_begin, groups);
+    return hipGetLastError();
+  });
 }
 
-// Occupancy cap of the row-split kernels: bytes of dynamic LDS requested per one-wavefront workgroup and
-// never touched.  What the memory system likes is a bounded number of requests in flight per CU, so the
-// cap follows the number of load streams per wavefront: 4 streams (g, m, x, e) -> 8 KiB = 20 wavefronts
-// per CU, 3 streams -> 7 KiB = 22, 2 streams (x only) -> no cap (measured: each is the best or within
-// 0.5 % of the best of a sweep, and 4-19 % better than the wrong one).
-uint32_t resolve_lds(const StepParams& p, const Tuning& tune) {
-  if (tune.lds_bytes >= 0) return static_cast<uint32_t>(tune.lds_bytes);
-  const int streams = 2 + (p.e != nullptr ? 1 : 0) + (p.m != nullptr ? 1 : 0);
-  return streams >= 4 ? 8192u : (streams == 3 ? 7168u : 0u);
-}
-
-int resolve_nontemporal(const StepParams& p, const Tuning& tune) {
-  int mode = tune.nontemporal;
-  if (mode < 0) {
-    // automatic: a working set that fits the 256 MiB last-level cache is better served by ordinary accesses
-    // (x, e, m come back next iteration; measured +7 % at 110-250 MB), a larger one by non-temporal ones (+10 %)
-    const uint64_t arrays = 2u + (p.e != nullptr ? 1u : 0u) + (p.m != nullptr ? 1u : 0u);
-    mode = static_cast<uint64_t>(p.W) * p.ld * 4u * arrays <= (256ull << 20) ? 0 : 1;
-  }
-  return mode;
-}
-
-template <int C, int NTMODE>
-hipError_t launch_rows_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t grid_size, uint32_t threads,
-                             uint32_t order, uint32_t lds, hipStream_t s) {
-  const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
-  const dim3 grid(grid_size), block(threads);
-  if (has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, true>), grid, block, lds, s, p, groups, tiles, order);
-  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, true, false>), grid, block, lds, s, p, groups, tiles, order);
-  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, true>), grid, block, lds, s, p, groups, tiles, order);
-  else hipLaunchKernelGGL((cser_step_rows_kernel<C, NTMODE, false, false>), grid, block, lds, s, p, groups, tiles, order);
-  return hipGetLastError();
-}
-
-template <int C>
-hipError_t launch_rows_c(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {
-  const uint32_t threads = static_cast<uint32_t>(tune.threads);
-  const uint64_t per_tile = static_cast<uint64_t>(threads) * C;
-  const uint64_t tiles64 = (groups + per_tile - 1) / per_tile;
-  const uint32_t order = tune.variant == 2 ? 1u : (tune.variant == 3 ? 2u : 0u);
-  uint64_t grid64 = tiles64 * p.W;
-  if (order == 2) grid64 = (grid64 + 7) / 8 * 8;
-  if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-  const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
-  const uint32_t lds = resolve_lds(p, tune);
-  switch (resolve_nontemporal(p, tune)) {
-    case 0: return launch_rows_flags<C, 0>(p, groups, tiles, grid, threads, order, lds, s);
-    case 2: return launch_rows_flags<C, 1>(p, groups, tiles, grid, threads, order, lds, s);
-    case 3: return launch_rows_flags<C, 2>(p, groups, tiles, grid, threads, order, lds, s);
-    default: return launch_rows_flags<C, 3>(p, groups, tiles, grid, threads, order, lds, s);
-  }
-}
-
-template <int NTMODE>
-hipError_t launch_tile_flags(const StepParams& p, uint32_t groups, uint32_t tiles, uint32_t grid_size, uint32_t order,
-                             uint32_t log2_w, uint32_t lds, hipStream_t s) {
-  const bool has_e = p.e != nullptr, has_m = p.m != nullptr;
-  const dim3 grid(grid_size), block(64);
-  if (has_e && has_m) hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, true, true>), grid, block, lds, s, p, groups, tiles, order, log2_w);
-  else if (has_e && !has_m) hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, true, false>), grid, block, lds, s, p, groups, tiles, order, log2_w);
-  else if (!has_e && has_m) hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, false, true>), grid, block, lds, s, p, groups, tiles, order, log2_w);
-  else hipLaunchKernelGGL((cser_step_tile_kernel<NTMODE, false, false>), grid, block, lds, s, p, groups, tiles, order, log2_w);
-  return hipGetLastError();
-}
-
-// The balanced kernel: W a power of two <= 64, one-wavefront workgroups, one column group per lane.
-hipError_t launch_tile(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {
-  uint32_t log2_w = 0;
-  while ((1u << log2_w) < p.W) ++log2_w;
+hipError_t launch_tile(const StepParams& p, uint32_t groups, bool nt, uint32_t lds, hipStream_t s) {
   const uint64_t tiles64 = (static_cast<uint64_t>(groups) + 63) / 64;
-  const uint32_t order = tune.variant == 2 ? 1u : (tune.variant == 3 ? 2u : 0u);
-  uint64_t grid64 = tiles64 * p.W;
-  if (order == 2) grid64 = (grid64 + 7) / 8 * 8;
-  if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-  const uint32_t tiles = static_cast<uint32_t>(tiles64), grid = static_cast<uint32_t>(grid64);
-  const uint32_t lds = resolve_lds(p, tune);
-  switch (resolve_nontemporal(p, tune)) {
-    case 0: return launch_tile_flags<0>(p, groups, tiles, grid, order, log2_w, lds, s);
-    case 2: return launch_tile_flags<1>(p, groups, tiles, grid, order, log2_w, lds, s);
-    case 3: return launch_tile_flags<2>(p, groups, tiles, grid, order, log2_w, lds, s);
-    default: return launch_tile_flags<3>(p, groups, tiles, grid, order, log2_w, lds, s);
-  }
+  const uint64_t grid64 = tiles64 * p.W;
+  if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;   // the C ABI rejects such sizes at create
+  const uint32_t tiles = static_cast<uint32_t>(tiles64);
+  const dim3 grid(static_cast<uint32_t>(grid64)), block(64);
+  return with_flags(nt, p.e != nullptr, p.m != nullptr, [&](auto NT, auto E, auto M) {
+    hipLaunchKernelGGL((cser_step_tile_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>), grid, block, lds, s,
+                       p, groups, tiles);
+    return hipGetLastError();
+  });
 }
 
-hipError_t launch_rows(const StepParams& p, uint32_t groups, const Tuning& tune, hipStream_t s) {
-  const bool w_pow2 = p.W <= 64 && (p.W & (p.W - 1)) == 0;
-  if (tune.balanced && w_pow2 && tune.threads == 64 && tune.cols_per_lane == 1) return launch_tile(p, groups, tune, s);
-  switch (tune.cols_per_lane) {
-    case 1: return launch_rows_c<1>(p, groups, tune, s);
-    case 4: return launch_rows_c<4>(p, groups, tune, s);
-    default: return launch_rows_c<2>(p, groups, tune, s);
+hipError_t launch_shared(const StepParams& p, uint32_t groups, bool nt, uint32_t lds, hipStream_t s) {
+  const dim3 grid((groups + 63u) / 64u), block(64u * p.W);
+  return with_flags(nt, p.e != nullptr, p.m != nullptr, [&](auto NT, auto E, auto M) {
+    hipLaunchKernelGGL((cser_step_shared_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>), grid, block, lds,
+                       s, p, groups);
+    return hipGetLastError();
+  });
+}
+
+// Smallest dynamic-LDS request (a multiple of 256 bytes, at least `needed`, at most 64 KiB) under which the
+// runtime's occupancy calculator fits no more than `want` workgroups of `threads` lanes of kernel `fn` on a CU;
+// want = 0 asks for no cap.  *resident receives what the calculator reports for the request returned.
+hipError_t cap_by_lds(const void* fn, uint32_t threads, uint32_t needed, uint32_t want, uint32_t* lds, uint32_t* resident) {
+  auto fits = [&](uint32_t bytes, int* n) {
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(n, fn, static_cast<int>(threads), bytes);
+  };
+  int n = 0;
+  uint32_t lo = (needed + 255u) / 256u, hi = 65536u / 256u;   // in units of 256 bytes
+  hipError_t err = fits(needed, &n);
+  if (err != hipSuccess) return err;
+  if (want == 0 || static_cast<uint32_t>(n) <= want) {
+    *lds = needed;
+    *resident = static_cast<uint32_t>(n);
+    return hipSuccess;
   }
+  err = fits(hi * 256u, &n);
+  if (err != hipSuccess) return err;
+  if (static_cast<uint32_t>(n) > want) {   // even the largest request leaves more than wanted: take it
+    *lds = hi * 256u;
+    *resident = static_cast<uint32_t>(n);
+    return hipSuccess;
+  }
+  if (lo > 0) lo -= 1;   // fits(lo) > want holds for the request `needed`, hence for anything below it
+  while (hi - lo > 1) {   // invariant: fits(lo) > want >= fits(hi)
+    const uint32_t mid = (lo + hi) / 2;
+    err = fits(mid * 256u, &n);
+    if (err != hipSuccess) return err;
+    if (static_cast<uint32_t>(n) > want) lo = mid;
+    else hi = mid;
+  }
+  err = fits(hi * 256u, &n);
+  if (err != hipSuccess) return err;
+  *lds = hi * 256u;
+  *resident = static_cast<uint32_t>(n);
+  return hipSuccess;
 }
 
 }  // namespace
+
+// Residency: measured on the large workload, the one-wavefront kernel is fastest with about 20 resident
+// wavefronts per CU when a wavefront has 4 load streams (g, m, x, e), 22 with 3, uncapped with 2 (each is the best
+// or within 0.5 % of the best of a sweep, and 4-19 % better than the wrong one; below 14 it falls off steeply);
+// the LDS-shared kernels with about 24 wavefronts per CU.
+hipError_t resolve_caps(uint32_t W, bool has_e, bool has_m, bool nontemporal, const Tuning& tune, Caps* out) {
+  *out = Caps();
+  hipError_t err = hipSuccess;
+  if (W <= 64) {
+    const int streams = 2 + (has_e ? 1 : 0) + (has_m ? 1 : 0);
+    const uint32_t want = tune.tile_waves_per_cu >= 0 ? static_cast<uint32_t>(tune.tile_waves_per_cu)
+                                                      : (streams >= 4 ? 20u : (streams == 3 ? 22u : 0u));
+    const void* fn = with_flags(nontemporal, has_e, has_m, [](auto NT, auto E, auto M) {
+      return reinterpret_cast<const void*>(&cser_step_tile_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>);
+    });
+    err = cap_by_lds(fn, 64, 0, want, &out->tile_lds, &out->tile_resident);
+    if (err != hipSuccess) return err;
+  }
+  if (W <= 16) {
+    uint32_t want = tune.shared_groups_per_cu >= 0 ? static_cast<uint32_t>(tune.shared_groups_per_cu) : 24u / W;
+    if (tune.shared_groups_per_cu < 0 && want < 2) want = 2;
+    const void* fn = with_flags(nontemporal, has_e, has_m, [](auto NT, auto E, auto M) {
+      return reinterpret_cast<const void*>(&cser_step_shared_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>);
+    });
+    err = cap_by_lds(fn, 64 * W, W * 1024u, want, &out->shared_lds, &out->shared_resident);
+    if (err != hipSuccess) return err;
+    err = cap_by_lds(fn, 64 * W, 2u * W * 1024u, want, &out->shared_reset_lds, &out->shared_reset_resident);
+    if (err != hipSuccess) return err;
+    const void* rfn = nontemporal ? (has_e ? reinterpret_cast<const void*>(&cser_reset_shared_kernel<true, true>)
+                                          : reinterpret_cast<const void*>(&cser_reset_shared_kernel<true, false>))
+                                  : (has_e ? reinterpret_cast<const void*>(&cser_reset_shared_kernel<false, true>)
+                                          : reinterpret_cast<const void*>(&cser_reset_shared_kernel<false, false>));
+    err = cap_by_lds(rfn, 64 * W, W * 1024u, want, &out->reset_lds, &out->reset_resident);
+  }
+  return err;
+}
 
 hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint64_t t_stride, uint32_t count, uint32_t B,
                            uint32_t k, uint8_t* mask, uint32_t* idx, hipStream_t s) {
@@ -894,35 +908,74 @@ hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint6
   return hipGetLastError();
 }
 
-hipError_t launch_step(const StepParams& p, bool vectorised, const Tuning& tune, hipStream_t s) {
-  if (!vectorised) return launch_step_range<1>(p, 0, p.d, tune, s);
-  const uint64_t d4 = p.d & ~3ull;
-  hipError_t err = hipSuccess;
-  if (tune.variant == 0) err = launch_step_range<4>(p, 0, d4, tune, s);
-  else if (d4 > 0) err = launch_rows(p, static_cast<uint32_t>(d4 / 4), tune, s);
-  if (err != hipSuccess) return err;
-  return launch_step_range<1>(p, d4, p.d, tune, s);   // at most 3 trailing columns
+hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* idx_sorted, hipStream_t s) {
+  if (k == 0) return hipSuccess;
+  hipLaunchKernelGGL(ordered_list_kernel, dim3(1), dim3(1024), 0, s, mask, B, k, idx_sorted);
+  return hipGetLastError();
 }
 
-hipError_t launch_reset(const ResetParams& p, const uint8_t* mask, bool vectorised, hipStream_t s) {
+hipError_t launch_step(const StepParams& p, bool vectorised, bool nontemporal, const Tuning& tune, const Caps& caps,
+                       double sync_share, int* used, hipStream_t s) {
+  int kernel = kKernelGeneral;
+  if (vectorised) {
+    kernel = tune.kernel;
+    if (kernel == kKernelTile && p.W > 64) kernel = kKernelAuto;
+    if (kernel == kKernelShared && p.W > 16) kernel = kKernelAuto;
+    if (kernel == kKernelAuto) {
+      // the LDS-shared kernel moves the synchronised blocks' bytes faster and the others' slower than the
+      // one-wavefront kernel; measured break-even at somewhat more than half of the blocks
+      if (p.W <= 16 && sync_share >= 0.55) kernel = kKernelShared;
+      else if (p.W <= 64) kernel = kKernelTile;
+      else kernel = kKernelGeneral;
+    }
+  }
+  if (used) *used = kernel;
+  if (!vectorised) return launch_general<1>(p, 0, p.d, nontemporal, s);
+  const uint64_t d4 = p.d & ~3ull;
+  hipError_t err = hipSuccess;
+  if (d4 > 0) {
+    const uint32_t groups = static_cast<uint32_t>(d4 / 4);
+    if (kernel == kKernelTile) err = launch_tile(p, groups, nontemporal, caps.tile_lds, s);
+    else if (kernel == kKernelShared)
+      err = launch_shared(p, groups, nontemporal, p.reset_mask != nullptr ? caps.shared_reset_lds : caps.shared_lds, s);
+    else err = launch_general<4>(p, 0, d4, nontemporal, s);
+  }
+  if (err != hipSuccess) return err;
+  return launch_general<1>(p, d4, p.d, nontemporal, s);   // at most 3 trailing columns
+}
+
+hipError_t launch_reset(const ResetParams& p, const uint8_t* mask, bool vectorised, bool nontemporal, const Tuning& tune,
+                        const Caps& caps, hipStream_t s) {
   if (p.k == 0) return hipSuccess;
   const bool has_e = p.e != nullptr;
   uint64_t scalar_begin = 0;
   if (vectorised) {
     const uint32_t gpb = p.block / 4;
     const uint64_t total = static_cast<uint64_t>(p.k) * gpb;
-    const uint32_t grid = static_cast<uint32_t>((total + 255) / 256);
-    if (has_e) hipLaunchKernelGGL(cser_reset_kernel<true>, dim3(grid), dim3(256), 0, s, p, gpb, total);
-    else hipLaunchKernelGGL(cser_reset_kernel<false>, dim3(grid), dim3(256), 0, s, p, gpb, total);
+    if (p.W <= 16 && tune.kernel != kKernelGeneral) {
+      const dim3 grid(static_cast<uint32_t>((total + 63) / 64)), block(64u * p.W);
+      const uint32_t lds = caps.reset_lds > p.W * 1024u ? caps.reset_lds : p.W * 1024u;
+      if (nontemporal) {
+        if (has_e) hipLaunchKernelGGL((cser_reset_shared_kernel<true, true>), grid, block, lds, s, p, gpb, total);
+        else hipLaunchKernelGGL((cser_reset_shared_kernel<true, false>), grid, block, lds, s, p, gpb, total);
+      } else {
+        if (has_e) hipLaunchKernelGGL((cser_reset_shared_kernel<false, true>), grid, block, lds, s, p, gpb, total);
+        else hipLaunchKernelGGL((cser_reset_shared_kernel<false, false>), grid, block, lds, s, p, gpb, total);
+      }
+    } else {
+      const dim3 grid(static_cast<uint32_t>((total + 255) / 256)), block(256);
+      if (has_e) hipLaunchKernelGGL((cser_reset_general_kernel<4, true>), grid, block, 0, s, p, mask, gpb, total, 0);
+      else hipLaunchKernelGGL((cser_reset_general_kernel<4, false>), grid, block, 0, s, p, mask, gpb, total, 0);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     scalar_begin = p.d & ~3ull;
   }
   if (scalar_begin >= p.d) return hipSuccess;
   const uint64_t n = p.d - scalar_begin;
-  const uint32_t grid = static_cast<uint32_t>((n + 255) / 256);
-  if (has_e) hipLaunchKernelGGL(cser_reset_scalar_kernel<true>, dim3(grid), dim3(256), 0, s, p, mask, scalar_begin, p.d);
-  else hipLaunchKernelGGL(cser_reset_scalar_kernel<false>, dim3(grid), dim3(256), 0, s, p, mask, scalar_begin, p.d);
+  const dim3 grid(static_cast<uint32_t>((n + 255) / 256)), block(256);
+  if (has_e) hipLaunchKernelGGL((cser_reset_general_kernel<1, true>), grid, block, 0, s, p, mask, 0, n, scalar_begin);
+  else hipLaunchKernelGGL((cser_reset_general_kernel<1, false>), grid, block, 0, s, p, mask, 0, n, scalar_begin);
   return hipGetLastError();
 }
 
@@ -937,8 +990,7 @@ hipError_t launch_fill_zero(float* ptr, uint64_t n, hipStream_t s) {
 hipError_t launch_copy(void* dst, const void* src, uint64_t n_bytes, hipStream_t s) {
   const uint64_t n16 = n_bytes / 16;
   if (n16 == 0) return hipSuccess;
-  // 256-lane workgroups, no occupancy cap: measured best for this two-stream copy (6.5 TB/s; the
-  // fused-step kernel's own shape, one wavefront per workgroup with 16 per CU, copies at 5.8 TB/s)
+  // 256-lane workgroups, no occupancy cap: measured best for this two-stream copy
   const uint64_t grid = (n16 + 255) / 256;
   hipLaunchKernelGGL(copy_kernel, dim3(static_cast<uint32_t>(grid)), dim3(256), 0, s, static_cast<f4*>(dst),
                      static_cast<const f4*>(src), n16);

@@ -62,6 +62,21 @@ def sweep_workloads():
     return out
 
 
+# Appendix C, Table 4 ("Compressor configurations"), optimizer CSER: for each overall compression ratio the tuned
+# (R_C2, R_C1, H) = (per-iteration compressor, error-reset compressor, reset interval).  Section 5.1:
+# overall = 1 / (1/R_C2 + 1/(R_C1 H)).
+TABLE4_CSER = ((2, 4, 2, 2), (4, 8, 2, 4), (8, 16, 2, 8), (16, 32, 8, 4), (32, 64, 8, 8), (64, 128, 8, 16),
+               (128, 256, 4, 64), (256, 512, 16, 32), (512, 1024, 8, 128), (1024, 2048, 32, 64))
+
+
+def table4_workloads():
+    """The ten CSER rows of the paper's Table 4 at the large-CNN size (block 1024, 8 workers), long enough for at
+    least two error resets each."""
+    base = WORKLOADS["large_cnn"]
+    return [replace(base, name=f"table4_R{overall}", R_step=r_step, R_reset=r_reset, H=H, seed=5, steps=max(64, 2 * H))
+            for overall, r_step, r_reset, H in TABLE4_CSER]
+
+
 def _generator(device, *key) -> torch.Generator:
     """A torch generator on `device`, seeded by mixing the integers in `key` (splitmix-style)."""
     s = 0x9E3779B97F4A7C15

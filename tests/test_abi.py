@@ -11,19 +11,22 @@ from paper_2007_13221_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "cser.h")).read()
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(cser_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
-    names = _declared()
+    names = _declared("cser.h")
     assert "cser_create" in names and "cser_step" in names and "cser_error_reset" in names and "cser_destroy" in names
+    measure = _declared("cser_measure.h")
+    assert "cser_set_tuning" in measure and not set(measure) & set(names)
     lib = ctypes.CDLL(B.LIBRARY)
-    for name in names:
+    for name in names + measure:
         assert hasattr(lib, name), name
-    assert sorted(B.EXPORTS) == names          # the binding covers the whole header, nothing more
+    assert sorted(B.EXPORTS) == names          # the binding covers both headers, nothing more
+    assert sorted(B.MEASURE_EXPORTS) == measure
 
 
 def test_config_struct_layout_matches_the_header():
@@ -74,6 +77,17 @@ def test_overall_ratio_matches_the_printed_table4_rows():
         assert B.cser_overall_ratio(cfg) == pytest.approx(overall, rel=1e-12)
     # the large workload mirrors the 256x row's pattern with R_step halved: 1 / (1/256 + 1/512) = 170.67
     assert B.cser_overall_ratio(B.make_config(1000, 8, 10, 256, 16, 32, 0.1, 0.9, 0)) == pytest.approx(512 / 3)
+
+
+def test_table4_workloads_carry_the_printed_rows():
+    from paper_2007_13221_amd import inputs as I
+    rows = [tuple(int(v) for v in l.split()) for l in open(os.path.join(ROOT, "tests", "golden", "table4_cser_rows.txt"))
+            if l.strip() and l[0] != "#"]
+    assert tuple(rows) == I.TABLE4_CSER
+    for wl, (overall, r_step, r_reset, H) in zip(I.table4_workloads(), rows):
+        assert (wl.R_step, wl.R_reset, wl.H) == (r_step, r_reset, H) and wl.steps >= 2 * H and wl.d == 25_557_032
+        cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed)
+        assert B.cser_overall_ratio(cfg) == pytest.approx(overall, rel=1e-12)
 
 
 def test_presets_of_the_special_cases():

@@ -1,13 +1,18 @@
 """Full-size GPU parity in the launch configuration bench.py times.
 
 At d = 25.6 M (and 335 M) the oracle cannot run the whole vector in test time, but every block
-evolves independently given the global block choice, so the oracle simulates sampled blocks
-(first, last with its ragged tail, blocks chosen by C_step and by C_reset at known iterations, and
-random ones) bit for bit, while properties that hold at any size cover every element: Lemma 1
-(x_i - e_i common to all workers) and the mean-model identity from the proofs
-(xbar_t = xbar_{t-1} - mean_i p_{i,t}), evaluated in float64 with torch as an independent check.
+evolves independently given the global block choice (which the oracle always makes over all B
+blocks), so the oracle simulates contiguous RANGES of blocks bit for bit: the range that starts at
+block 0, the one that ends with the ragged last block, one that crosses a multiple of 2^20 columns,
+ranges centred on blocks that C_step and C_reset chose at known iterations, and random ones, until
+the stated fraction of the blocks is covered.  Every element of those ranges is compared with the
+oracle (x, e, m, all workers), so a block treated as chosen when it is not, or the reverse, fails.
+Two properties that hold at any size cover every element besides: Lemma 1 (x_i - e_i common to
+all workers) and the mean-model identity from the proofs (xbar_t = xbar_{t-1} - mean_i p_{i,t}),
+evaluated in float64 with torch as an independent check.
 """
 from dataclasses import replace
+from fractions import Fraction
 
 import numpy as np
 import pytest
@@ -21,45 +26,90 @@ from tests.test_gpu_parity import assert_states_close
 pytestmark = pytest.mark.gpu
 
 
-def sample_blocks(wl, steps, rng, extra_reset_t=None):
+def block_ranges(wl, steps, fraction, rng, extra_reset_t=None, max_ranges=10):
+    """Disjoint block ranges [b0, b1) covering at least `fraction` of the B blocks."""
     Bn = wl.B
+    target = max(1, int(np.ceil(Bn * fraction)))
+    span = max(2, -(-target // max_ranges))          # blocks per range
     ks, kr = R.blocks_kept(Bn, wl.R_step), R.blocks_kept(Bn, wl.R_reset)
-    blocks = {0, 1 % Bn, Bn - 1, max(Bn - 2, 0)}
-    for t in sorted({1, 2, steps}):
-        blocks.update(int(b) for b in R.select_blocks(wl.seed, 0, t, Bn, ks)[0][:2])
+    centres = [0, Bn - 1]
+    # a block boundary region that contains a multiple of 2^20 columns (tile and 32-bit offset arithmetic)
+    for mult in (1, 1 << 11):                         # columns 2^20 and 2^31
+        col = mult << 20
+        if col < wl.d:
+            centres.append(col // wl.block)
+    if ks:
+        for t in (1, steps):
+            centres.append(int(R.select_blocks(wl.seed, 0, t, Bn, ks)[0][0]))
     reset_ts = [t for t in range(1, steps + 1) if wl.H and t % wl.H == 0]
     if extra_reset_t:
         reset_ts.append(extra_reset_t)
-    for t in reset_ts[:2] + reset_ts[-1:]:
-        blocks.update(int(b) for b in R.select_blocks(wl.seed, 1, t, Bn, kr)[0][:3])
-    blocks.update(int(b) for b in rng.integers(0, Bn, size=4))
-    return sorted(blocks)
+    for t in reset_ts[:1] + reset_ts[-1:]:
+        centres.append(int(R.select_blocks(wl.seed, 1, t, Bn, kr)[0][0]))
+    ranges = []
+
+    def covered():
+        return sum(b1 - b0 for b0, b1 in ranges)
+
+    def add(centre):
+        b0 = max(0, min(centre - span // 2, Bn - span))
+        b1 = min(Bn, b0 + span)
+        for i, (a0, a1) in enumerate(ranges):         # merge with a range it touches
+            if b0 <= a1 and a0 <= b1:
+                ranges[i] = (min(a0, b0), max(a1, b1))
+                return
+        ranges.append((b0, b1))
+
+    for c in centres:
+        add(c)
+    while covered() < target:
+        add(int(rng.integers(0, Bn)))
+    merged = []
+    for b0, b1 in sorted(ranges):
+        if merged and b0 <= merged[-1][1]:
+            merged[-1] = (merged[-1][0], max(merged[-1][1], b1))
+        else:
+            merged.append((b0, b1))
+    return merged
 
 
-def run_sliced(wl, steps, check_mean_model=True, forced_reset=False):
+def run_ranges(wl, steps, fraction, check_mean_model=True, forced_reset=False, with_error=True, max_ranges=10):
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(wl.seed + 1000)
     ld = wl.ld
     x = I.initial_model(wl, dev)
     x0_row = x[0, :wl.d].clone()
     cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=ld)
-    opt = B.CSER(cfg, x)
-    blocks = sample_blocks(wl, steps, rng, extra_reset_t=steps if forced_reset else None)
+    opt = B.CSER(cfg, x, with_error=with_error)
+    ranges = block_ranges(wl, steps, fraction, rng, extra_reset_t=steps if forced_reset else None,
+                          max_ranges=max_ranges)
     oracles = []
-    for b in blocks:
-        c0, c1 = b * wl.block, min(wl.d, (b + 1) * wl.block)
-        oracles.append((c0, c1, R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum,
-                                             wl.seed, x0_row[c0:c1].cpu().numpy(), b0=b, b1=b + 1)))
+    for b0, b1 in ranges:
+        c0, c1 = b0 * wl.block, min(wl.d, b1 * wl.block)
+        oracles.append((b0, b1, c0, c1, R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr,
+                                                    wl.momentum, wl.seed, x0_row[c0:c1].cpu().numpy(), b0=b0, b1=b1,
+                                                    with_error=with_error)))
     g = torch.zeros(wl.W, ld, device=dev, dtype=torch.float32)
     if check_mean_model:
         m64 = torch.zeros(wl.W, wl.d, device=dev, dtype=torch.float64)
         xbar = x0_row.double()
         beta, eta = float(np.float32(wl.momentum)), float(np.float32(wl.lr))
+    Bn = wl.B
+    ks, kr = R.blocks_kept(Bn, wl.R_step), R.blocks_kept(Bn, wl.R_reset)
+    step_events = reset_events = 0     # (block, iteration) pairs inside the ranges that each compressor chose
+
+    def chosen_inside(mask):
+        return sum(int(mask[b0:b1].sum()) for b0, b1, _, _, _ in oracles)
+
     for t in range(1, steps + 1):
         I.gradient(wl, t, dev, out=g)
         opt.step(g)
-        for c0, c1, o in oracles:
+        for _, _, c0, c1, o in oracles:
             o.step(g[:, c0:c1].cpu().numpy())
+        if ks:
+            step_events += chosen_inside(R.select_blocks(wl.seed, 0, t, Bn, ks)[1])
+        if wl.H and t % wl.H == 0:
+            reset_events += chosen_inside(R.select_blocks(wl.seed, 1, t, Bn, kr)[1])
         if check_mean_model:
             g64 = g[:, :wl.d].double()
             m64.mul_(beta).add_(g64)
@@ -67,51 +117,80 @@ def run_sliced(wl, steps, check_mean_model=True, forced_reset=False):
             del g64
     if forced_reset:
         opt.error_reset()
-        for _, _, o in oracles:
+        for _, _, _, _, o in oracles:
             o.error_reset()
+        reset_events += chosen_inside(R.select_blocks(wl.seed, 1, steps, Bn, kr)[1])
     torch.cuda.synchronize()
 
     not_identical = 0
-    for c0, c1, o in oracles:
+    compared = 0
+    for _, _, c0, c1, o in oracles:
         not_identical += assert_states_close("x", opt.x[:, c0:c1].cpu().numpy(), o.x)
-        not_identical += assert_states_close("e", opt.e[:, c0:c1].cpu().numpy(), o.e)
+        if with_error:
+            not_identical += assert_states_close("e", opt.e[:, c0:c1].cpu().numpy(), o.e)
         not_identical += assert_states_close("m", opt.m[:, c0:c1].cpu().numpy(), o.m)
-    assert not_identical == 0, f"{not_identical} sampled elements not bit-identical"
+        compared += c1 - c0
+    blocks = sum(b1 - b0 for b0, b1, _, _, _ in oracles)
+    print(f"\n[full-size parity] {wl.name}: d={wl.d} block={wl.block} R_step={wl.R_step} R_reset={wl.R_reset} H={wl.H} "
+          f"steps={steps}{' + forced reset' if forced_reset else ''}: {len(oracles)} ranges, {blocks} of {Bn} blocks "
+          f"= {blocks / Bn:.4f} of the blocks ({compared} columns x {wl.W} workers, every element of x"
+          f"{', e' if with_error else ''}, m); inside them C_step chose {step_events} (block, iteration) pairs, "
+          f"C_reset {reset_events}; {not_identical} elements not bit-identical")
+    assert Fraction(blocks, Bn) >= Fraction(fraction).limit_denominator(1 << 20), (blocks, Bn, fraction)
+    assert ks == 0 or step_events > 0
+    assert reset_events > 0 or not (forced_reset or (wl.H and steps >= wl.H))
+    assert not_identical == 0, f"{not_identical} compared elements not bit-identical"
 
-    # Lemma 1 on every column: x_i - e_i is the same for all workers, up to fp32 rounding of the
-    # accumulated updates (each step rounds x and e separately)
-    z = opt.x[:, :wl.d].double() - opt.e[:, :wl.d].double()
-    spread = (z - z[0]).abs().max().item()
-    scale = max(1.0, opt.x.abs().max().item())
-    assert spread <= steps * 2.0 ** -22 * scale, spread
-    del z
+    if with_error:
+        # Lemma 1 on every column: x_i - e_i is the same for all workers, up to fp32 rounding of the
+        # accumulated updates (each step rounds x and e separately)
+        z = opt.x[:, :wl.d].double() - opt.e[:, :wl.d].double()
+        spread = (z - z[0]).abs().max().item()
+        scale = max(1.0, opt.x.abs().max().item())
+        assert spread <= steps * 2.0 ** -22 * scale, spread
+        del z
     if check_mean_model:
+        scale = max(1.0, opt.x.abs().max().item())
         got = opt.x[:, :wl.d].double().mean(dim=0)
         err = (got - xbar).abs().max().item()
         assert err <= steps * 2.0 ** -22 * scale, err
     # padding columns were never touched
     if ld > wl.d:
-        assert not opt.x[:, wl.d:].any() and not opt.e[:, wl.d:].any() and not opt.m[:, wl.d:].any()
+        assert not opt.x[:, wl.d:].any() and not opt.m[:, wl.d:].any()
+        assert not with_error or not opt.e[:, wl.d:].any()
     opt.close()
 
 
 def test_large_cnn_full_size_100_steps_with_three_resets():
-    run_sliced(I.WORKLOADS["large_cnn"], 100)
+    run_ranges(I.WORKLOADS["large_cnn"], 100, 1 / 16)
 
 
-@pytest.mark.parametrize("R_step,block,H", [(2, 64, 4), (1024, 4096, 4), (8, 256, 4), (32, 1024, 4)])
-def test_compression_sweep_corners_full_size(R_step, block, H):
+def test_large_cnn_full_size_implementation_two():
+    run_ranges(I.WORKLOADS["large_cnn"], 40, 1 / 64, check_mean_model=False, with_error=False)
+
+
+@pytest.mark.parametrize("R_step,block,H", [(2, 64, 4), (1024, 4096, 4), (8, 256, 32), (32, 1024, 4), (2, 4096, 32),
+                                            (1024, 64, 32), (256, 256, 4), (8, 1024, 32)])
+def test_compression_sweep_points_full_size_50_steps(R_step, block, H):
     wl = replace(I.WORKLOADS["large_cnn"], name="sweep", R_step=R_step, block=block, R_reset=16, H=H, seed=3)
-    run_sliced(wl, 6, check_mean_model=False)
+    # at block 64 the oracle's block choice over 399,329 blocks costs as much as the update: fewer, longer ranges
+    run_ranges(wl, 50, 1 / 64, check_mean_model=False, max_ranges=5 if block == 64 else 8)
 
 
-def test_transformer_sized_stress_with_forced_reset():
+@pytest.mark.parametrize("wl", I.table4_workloads(), ids=lambda w: f"{w.name}-Rstep{w.R_step}-Rreset{w.R_reset}-H{w.H}")
+def test_table4_compressor_configurations_full_size(wl):
+    """The ten CSER rows of the paper's Table 4 (Appendix C) at the large-CNN size: two reset periods each (H up to
+    128), from a reset of half of the blocks every second iteration to one of 1/32 of them every 64th."""
+    run_ranges(wl, max(2 * wl.H, 8), 1 / 64, check_mean_model=False, max_ranges=8)
+
+
+def test_transformer_sized_stress_20_steps_and_forced_reset():
     # 20 steps are fewer than H = 64, so the reset is forced once at the end, as the workload prescribes
     wl = I.WORKLOADS["transformer"]
-    run_sliced(wl, 6, check_mean_model=False, forced_reset=True)
+    run_ranges(wl, 20, 1 / 64, check_mean_model=False, forced_reset=True, max_ranges=8)
 
 
 def test_rows_longer_than_2_pow_31_columns():
     """Column and byte offsets beyond 32 bits: d = 2^31 + 4099 (ragged tail, d % 4 = 3), two workers, 69 GB resident."""
     wl = I.Workload("wide", 2**31 + 4099, 2, 4096, 64, 4, 2, 0.1, 0.9, 1e-2, 1e-3, 7, 3)
-    run_sliced(wl, 3, check_mean_model=False)
+    run_ranges(wl, 3, 1 / 256, check_mean_model=False, max_ranges=8)

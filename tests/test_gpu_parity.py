@@ -4,6 +4,8 @@ inputs.  Block indices and masks must be bit-exact; fp32 states must satisfy
 (written-out fused multiply-adds, in-order worker sum, true division) the two are in fact expected
 to agree bit for bit, which the tests also record.
 """
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -15,6 +17,11 @@ from paper_2007_13221_amd import inputs as I
 pytestmark = pytest.mark.gpu
 
 ABS_TOL, REL_TOL = 1e-7, 1e-6
+
+# launch shapes (measurement interface): every one must give the same bits
+K, NT, FUSE, TILE_CAP, SHARED_CAP = (B.CSER_TUNE_KERNEL, B.CSER_TUNE_NONTEMPORAL, B.CSER_TUNE_FUSE_RESET,
+                                     B.CSER_TUNE_TILE_WAVES_PER_CU, B.CSER_TUNE_SHARED_GROUPS_PER_CU)
+TILE, SHARED, GENERAL = B.KERNEL_TILE, B.KERNEL_SHARED, B.KERNEL_GENERAL
 
 
 def assert_states_close(name, got, want):
@@ -106,9 +113,10 @@ def test_selector_indices_and_masks_are_bit_exact(d, block, R_step, R_reset):
 
 
 # ---------------------------------------------------------------------------- named workloads
-@pytest.mark.parametrize("tuning", [None, {6: 0}, {8: 0}, {8: 0, 6: 0}, {4: 0}, {4: 0, 6: 0}],
-                         ids=["balanced-fused-reset", "balanced-separate-reset", "worker0-fused-reset",
-                              "worker0-separate-reset", "lane-walks-workers", "lane-walks-separate"])
+@pytest.mark.parametrize("tuning", [None, {FUSE: 0}, {K: TILE}, {K: SHARED}, {K: SHARED, FUSE: 0}, {K: GENERAL},
+                                    {K: GENERAL, FUSE: 0}],
+                         ids=["auto-fused-reset", "auto-separate-reset", "one-wavefront", "lds-shared",
+                              "lds-shared-separate-reset", "lane-walks-workers", "lane-walks-separate"])
 def test_tiny_workload_100_steps(tuning):
     wl = I.WORKLOADS["tiny"]
     diff = run_pair(wl, 100, check_every=20, tuning=tuning)
@@ -172,9 +180,10 @@ def test_misaligned_base_pointers():
 
 def test_implementation_two_without_residual_buffer():
     wl = _wl(d=20000, W=8, steps=16)
-    assert run_pair(wl, 16, with_error=False) == 0
-    assert run_pair(wl, 16, with_error=False, tuning={6: 0}) == 0
-    assert run_pair(_wl(d=20000, W=5, R_step=2, R_reset=2, H=1), 8, with_error=False) == 0
+    for tuning in (None, {FUSE: 0}, {K: SHARED}, {K: SHARED, FUSE: 0}, {K: GENERAL}):
+        assert run_pair(wl, 16, with_error=False, tuning=tuning) == 0
+    for tuning in (None, {K: SHARED}, {K: GENERAL}):
+        assert run_pair(_wl(d=20000, W=5, R_step=2, R_reset=2, H=1), 8, with_error=False, tuning=tuning) == 0
 
 
 def test_blocks_chosen_by_both_compressors_at_once():
@@ -182,24 +191,38 @@ def test_blocks_chosen_by_both_compressors_at_once():
     for kw in (dict(), dict(W=3), dict(block=6), dict(momentum=0.0)):
         wl = _wl(d=30000, R_step=2, R_reset=2, H=1, **kw)
         assert run_pair(wl, 10) == 0
-        assert run_pair(wl, 10, tuning={8: 0}) == 0
-        assert run_pair(wl, 10, tuning={4: 0}) == 0
+        for kernel in (TILE, SHARED, GENERAL):
+            assert run_pair(wl, 10, tuning={K: kernel}) == 0
 
 
 def test_no_momentum_buffer_is_algorithm_2():
     wl = _wl(d=20000, W=8, momentum=0.0)
-    assert run_pair(wl, 12, with_momentum=False) == 0
-    assert run_pair(wl, 12, with_momentum=False, with_error=False) == 0
+    for tuning in (None, {K: SHARED}, {K: GENERAL}):
+        assert run_pair(wl, 12, with_momentum=False, tuning=tuning) == 0
+        assert run_pair(wl, 12, with_momentum=False, with_error=False, tuning=tuning) == 0
 
 
-@pytest.mark.parametrize("tuning", [{4: 0}, {4: 0, 0: 1}, {4: 0, 0: 7}, {4: 0, 1: 0}, {4: 0, 2: 1}, {4: 0, 2: 2},
-                                    {4: 0, 2: 8}, {4: 0, 0: 3, 1: 0, 2: 8}, {4: 0, 3: 64}, {4: 0, 3: 1024},
-                                    {4: 1, 5: 2}, {4: 1, 5: 4, 3: 512}, {4: 2}, {4: 2, 5: 2, 3: 128}, {4: 3},
-                                    {4: 3, 3: 64, 5: 4}, {1: 0}, {1: 2}, {1: 3}, {3: 256}, {3: 1024}, {6: 0}, {6: 0, 4: 0}, {8: 0}, {8: 0, 6: 0},
-                                    {8: 0, 1: 0}, {4: 2, 8: 1}, {4: 3, 8: 1, 1: 0}])
+@pytest.mark.parametrize("tuning", [{K: TILE}, {K: TILE, NT: 0}, {K: TILE, NT: 1}, {K: TILE, TILE_CAP: 0}, {K: TILE, TILE_CAP: 7},
+                                    {K: TILE, FUSE: 0}, {K: SHARED}, {K: SHARED, NT: 0}, {K: SHARED, NT: 1},
+                                    {K: SHARED, SHARED_CAP: 0}, {K: SHARED, SHARED_CAP: 1}, {K: SHARED, FUSE: 0},
+                                    {K: GENERAL}, {K: GENERAL, NT: 1}, {K: GENERAL, FUSE: 0}, {NT: 1}, {FUSE: 0}],
+                         ids=lambda t: "-".join(f"{k}={v}" for k, v in t.items()))
 def test_results_do_not_depend_on_launch_shape(tuning):
     wl = _wl(d=30000, W=8, steps=8)
     assert run_pair(wl, 8, tuning=tuning) == 0
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 5, 6, 7, 12, 13, 16, 17, 31, 33, 48, 64, 65])
+@pytest.mark.parametrize("R_step", [1, 2, 5])
+def test_every_worker_count_in_every_kernel_that_takes_it(W, R_step):
+    """The one-wavefront kernel shares a tile's synchronised column groups among its W workgroups in slices of
+    floor(64 / W) groups (two rounds when W does not divide 64); the LDS-shared kernel has W wavefronts per
+    workgroup; beyond 64 workers a lane walks the worker axis."""
+    wl = _wl(d=2500, W=W, block=8, R_step=R_step, R_reset=2, H=2, steps=4)
+    kernels = [None] + ([TILE] if W <= 64 else []) + ([SHARED] if W <= 16 else []) + [GENERAL]
+    for kernel in kernels:
+        assert run_pair(wl, 4, tuning=None if kernel is None else {K: kernel}) == 0
+        assert run_pair(wl, 4, with_error=False, tuning=None if kernel is None else {K: kernel}) == 0
 
 
 def test_learning_rate_schedule():
@@ -274,7 +297,7 @@ def _random_cases(n, seed):
             lr=float(rng.choice([0.1, 0.01, 1.0])), seed=int(rng.integers(0, 2**62)),
             ld=int(rng.choice([d, -(-d // 4) * 4, -(-d // 64) * 64, -(-d // 1024) * 1024])),
             with_error=bool(rng.integers(0, 2)), with_momentum=bool(momentum != 0.0 or rng.integers(0, 2)),
-            tuning=[None, {4: 0}, {4: 2, 5: 2}, {6: 0}, {3: 256, 5: 4}, {4: 3, 1: 0}, {8: 0}, None][int(rng.integers(0, 8))]))
+            tuning=[None, {K: GENERAL}, {K: SHARED}, {FUSE: 0}, {K: TILE, NT: 1}, {K: SHARED, NT: 0}, {K: TILE}, None][int(rng.integers(0, 8))]))
     return cases
 
 
@@ -392,7 +415,7 @@ def test_gpu_run_stays_within_rounding_of_the_float64_oracle():
     opt.close()
 
 
-def test_profile_counters_and_copy_probe():
+def test_profile_timers_counters_and_copy_probe():
     dev = torch.device("cuda:0")
     wl = _wl(d=100000, W=8, H=2)
     cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
@@ -403,13 +426,21 @@ def test_profile_counters_and_copy_probe():
         opt.step(g)
     assert B.cser_profile_read(opt.ctx, 0)[1] == 6
     assert B.cser_profile_read(opt.ctx, 1)[1] == 0      # resets ran inside the fused-step kernel
+    c = B.cser_measure_counters(opt.ctx)
+    # R_step = 4, R_reset = 2: a quarter of the blocks is synchronised on ordinary iterations (one-wavefront kernel),
+    # five eighths on reset iterations (LDS-shared kernel)
+    assert (c["steps"], c["window_draws"], c["resets_fused"], c["resets_separate"]) == (6, 1, 3, 0)
+    assert (c["launches_tile"], c["launches_shared"], c["launches_general"]) == (3, 3, 0)
     B.cser_profile_clear(opt.ctx)
-    B.cser_set_tuning(opt.ctx, 6, 0)                     # separate reset kernel
+    B.cser_set_tuning(opt.ctx, FUSE, 0)                  # separate reset kernel
     for _ in range(6):
         opt.step(g)
     ms0, n0 = B.cser_profile_read(opt.ctx, 0)
     ms1, n1 = B.cser_profile_read(opt.ctx, 1)
     assert n0 == 6 and n1 == 3 and ms0 > 0 and ms1 > 0
+    c = B.cser_measure_counters(opt.ctx)
+    assert (c["steps"], c["window_draws"], c["resets_fused"], c["resets_separate"]) == (12, 2, 3, 3)
+    assert (c["launches_tile"], c["launches_shared"]) == (9, 3)
     B.cser_profile_clear(opt.ctx)
     assert B.cser_profile_read(opt.ctx, 0) == (0.0, 0)
     opt.close()
@@ -418,3 +449,62 @@ def test_profile_counters_and_copy_probe():
     B.cser_copy_probe(dst, src, src.numel() * 4)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
+
+
+def test_residency_caps_are_what_the_launches_get():
+    """The kernels bound the wavefronts resident on a CU by the size of their dynamic LDS request; the request is
+    chosen with the runtime's occupancy calculator, and what it reports for the chosen request is the cap asked for."""
+    dev = torch.device("cuda:0")
+    for with_error, with_momentum, want_tile in ((True, True, 20), (False, True, 22), (True, False, 22), (False, False, None)):
+        wl = _wl(d=100000, W=8, momentum=0.9 if with_momentum else 0.0)
+        cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+        opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=with_error, with_momentum=with_momentum)
+        r = B.cser_measure_residency(opt.ctx)
+        if want_tile is None:
+            assert r["tile_lds"] == 0 and r["tile_groups_per_cu"] >= 24     # two load streams: no cap
+        else:
+            assert r["tile_groups_per_cu"] == want_tile, r
+        assert r["shared_groups_per_cu"] == 3 and r["shared_lds"] >= 8 * 1024, r          # 24 wavefronts per CU at W = 8
+        assert r["shared_reset_groups_per_cu"] == 3 and r["shared_reset_lds"] >= 16 * 1024, r
+        assert r["reset_groups_per_cu"] == 3, r
+        B.cser_set_tuning(opt.ctx, TILE_CAP, 12)
+        B.cser_set_tuning(opt.ctx, SHARED_CAP, 2)
+        r = B.cser_measure_residency(opt.ctx)
+        assert r["tile_groups_per_cu"] == 12 and r["shared_groups_per_cu"] == 2 and r["reset_groups_per_cu"] == 2, r
+        opt.close()
+    wl = _wl(d=100000, W=3)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, I.initial_model(wl, dev))
+    assert B.cser_measure_residency(opt.ctx)["shared_groups_per_cu"] == 8       # 24 / 3
+    opt.close()
+
+
+def test_many_steps_in_one_call_equal_the_same_steps_one_by_one():
+    dev = torch.device("cuda:0")
+    wl = _wl(d=9000, W=4, H=3)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    grads = [I.gradient(wl, t, dev) for t in range(1, 41)]
+    one = B.CSER(cfg, I.initial_model(wl, dev))
+    for g in grads:
+        one.step(g)
+    many = B.CSER(cfg, I.initial_model(wl, dev))
+    assert many.step_many(grads[:7]) == 7
+    prepared = B.gradient_list(grads[7:])
+    assert many.step_many(prepared) == 33
+    assert many.step_many([]) == 0
+    torch.cuda.synchronize()
+    assert B.cser_get_step(many.ctx) == B.cser_get_step(one.ctx) == 40
+    for name in ("x", "e", "m"):
+        assert torch.equal(getattr(one, name), getattr(many, name))
+    o = R.OracleCSER(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed,
+                     I.initial_model_row(wl, dev).cpu().numpy())
+    for g in grads:
+        o.step(g[:, :wl.d].cpu().numpy())
+    for name in ("x", "e", "m"):
+        assert assert_states_close(name, getattr(many, name)[:, :wl.d].cpu().numpy(), getattr(o, name)) == 0
+    # a bad pointer in the list stops the call there and reports how far it got
+    bad = (ctypes.c_void_p * 3)(grads[0].data_ptr(), grads[1].data_ptr() + 2, grads[2].data_ptr())
+    done = ctypes.c_uint32()
+    assert B._lib().cser_step_many(many.ctx, bad, 3, None, ctypes.byref(done)) == B.CSER_EALIGN and done.value == 1
+    one.close()
+    many.close()
