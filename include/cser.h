@@ -150,6 +150,22 @@ int cser_set_step(cser_ctx* ctx, uint64_t t);
  */
 int cser_step_many(cser_ctx* ctx, const float* const* g_list, uint32_t n, void* hip_stream, uint32_t* done);
 
+/*
+ * cser_step() for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No context: the call carries out iteration t of the configuration
+ * *cfg on the caller's buffers (same meaning, layout and arithmetic as cser_create + cser_step; e and m
+ * may be NULL as there; nothing is zero-filled, the caller keeps t) and allocates nothing, on the host
+ * or on the device.  The block masks of C_step (and, when H > 0 and t mod H = 0, of C_reset) are drawn
+ * into a fixed device array of 2 * CSER_STATIC_MAX_BLOCKS bytes that the library holds on every GPU it
+ * has run on until the process ends; a configuration with more than CSER_STATIC_MAX_BLOCKS blocks
+ * returns CSER_ERANGE.  All calls on one GPU share that array: calls that overlap on one GPU (different
+ * streams, different threads) race; calls on one stream are ordered.  The first call on a device looks up
+ * the array's address and the launch shapes for that device.
+ */
+#define CSER_STATIC_MAX_BLOCKS 524288u
+int cser_step_static(const cser_config* cfg, uint64_t t, float* x, float* e, float* m, const float* g,
+                     void* hip_stream);
+
 const char* cser_strerror(int status);
 const char* cser_last_hip_error(void); /* text of the last HIP error seen by this thread, "" if none */
 

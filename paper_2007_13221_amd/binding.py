@@ -14,8 +14,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIBRARY = os.path.join(_HERE, "libcser_hip.so")
 
 CSER_OK, CSER_EINVAL, CSER_EALIGN, CSER_ENOMEM, CSER_EHIP, CSER_ERANGE = 0, -1, -2, -3, -4, -5
+CSER_STATIC_MAX_BLOCKS = 524288
 
-EXPORTS = ("cser_create", "cser_step", "cser_step_many", "cser_error_reset", "cser_destroy", "cser_select_blocks",
+EXPORTS = ("cser_create", "cser_step", "cser_step_many", "cser_step_static", "cser_error_reset", "cser_destroy", "cser_select_blocks",
            "cser_preset_csea", "cser_preset_cser_pl", "cser_overall_ratio",
            "cser_block_counts", "cser_set_lr", "cser_get_step", "cser_set_step", "cser_strerror", "cser_last_hip_error")
 MEASURE_EXPORTS = ("cser_profile_enable", "cser_profile_read", "cser_profile_clear", "cser_set_tuning",
@@ -70,6 +71,7 @@ def _lib():
         L.cser_create.argtypes = [ctypes.POINTER(cser_config), vp, vp, vp, vp, ctypes.POINTER(vp)]
         L.cser_step.argtypes = [vp, vp, vp]
         L.cser_step_many.argtypes = [vp, vp, u32, vp, ctypes.POINTER(u32)]
+        L.cser_step_static.argtypes = [ctypes.POINTER(cser_config), u64, vp, vp, vp, vp, vp]
         L.cser_error_reset.argtypes = [vp, vp]
         L.cser_destroy.argtypes = [vp]
         L.cser_select_blocks.argtypes = [vp, ctypes.c_int, u64, vp, vp, ctypes.POINTER(u32)]
@@ -143,6 +145,12 @@ def cser_step_many(ctx, grads, stream=None):
     done = ctypes.c_uint32()
     _check(_lib().cser_step_many(ctx, arr, n, _stream(stream), ctypes.byref(done)), "cser_step_many")
     return done.value
+
+
+def cser_step_static(cfg: cser_config, t, x, e, m, g, stream=None):
+    """Iteration t of configuration cfg on the caller's buffers, without a context and without any allocation."""
+    _check(_lib().cser_step_static(ctypes.byref(cfg), int(t), _ptr(x), _ptr(e), _ptr(m), _ptr(g), _stream(stream)),
+           "cser_step_static")
 
 
 def gradient_list(grads):

@@ -7,6 +7,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -448,6 +449,104 @@ const char* cser_strerror(int status) {
 }
 
 const char* cser_last_hip_error(void) { return g_last_hip_error.c_str(); }
+
+// ---------------------------------------------------------------- the entry point that allocates nothing
+}  // extern "C"
+
+namespace {
+
+// Block masks of cser_step_static: C_step's in the first half, C_reset's in the second.  One copy per GPU, held
+// until the process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels and
+// launches use the device address looked up below.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[2u * CSER_STATIC_MAX_BLOCKS];
+
+constexpr int kMaxStaticDevices = 64;
+
+struct StaticDevice {
+  unsigned char* scratch_ptr = nullptr;   // device address of `scratch` on this GPU
+  // launch shapes by [W, or 0 beyond 16 workers][has e][has m][non-temporal]
+  bool caps_known[17][2][2][2] = {};
+  cser::Caps caps[17][2][2][2];
+};
+
+StaticDevice g_static_devices[kMaxStaticDevices];
+std::mutex g_static_mutex;
+
+// Set-up for the current device: the address of this GPU's copy of `scratch` (once per device) and the launch
+// shapes of this (W, buffers) combination (once per combination); afterwards a lookup.
+int static_setup(const cser_config& c, bool has_e, bool has_m, bool nontemporal, unsigned char** ptr, cser::Caps* caps) {
+  int device = -1;
+  CSER_HIP(hipGetDevice(&device));
+  if (device < 0 || device >= kMaxStaticDevices) return CSER_ERANGE;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticDevice& sd = g_static_devices[device];
+  if (sd.scratch_ptr == nullptr) {
+    void* address = nullptr;
+    CSER_HIP(hipGetSymbolAddress(&address, HIP_SYMBOL(scratch)));
+    if (address == nullptr) return hip_failed(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+    sd.scratch_ptr = static_cast<unsigned char*>(address);
+  }
+  *ptr = sd.scratch_ptr;
+  *caps = cser::Caps();
+  if (c.block % 4 == 0) {
+    const uint32_t w = c.W <= 16 ? c.W : 0u;
+    cser::Caps& slot = sd.caps[w][has_e][has_m][nontemporal];
+    if (!sd.caps_known[w][has_e][has_m][nontemporal]) {
+      CSER_HIP(cser::resolve_caps(c.W, has_e, has_m, nontemporal, cser::Tuning(), &slot));
+      sd.caps_known[w][has_e][has_m][nontemporal] = true;
+    }
+    *caps = slot;
+  }
+  return CSER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cser_step_static(const cser_config* cfg, uint64_t t, float* x, float* e, float* m, const float* g,
+                     void* hip_stream) {
+  const int bad = validate(cfg, x, e, m);
+  if (bad != CSER_OK) return bad;
+  if (!g) return CSER_EINVAL;
+  if (!aligned(g, 4)) return CSER_EALIGN;
+  const uint64_t B = ceil_div(cfg->d, cfg->block);
+  if (B > CSER_STATIC_MAX_BLOCKS) return CSER_ERANGE;
+  const bool has_e = e != nullptr, has_m = m != nullptr;
+  const bool nontemporal = wants_nontemporal(*cfg, has_e, has_m, -1);
+  unsigned char* masks = nullptr;
+  cser::Caps caps;
+  int rc = static_setup(*cfg, has_e, has_m, nontemporal, &masks, &caps);
+  if (rc != CSER_OK) return rc;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const uint32_t k_step = cfg->R_step == 0 ? 0u : static_cast<uint32_t>(ceil_div(B, cfg->R_step));
+  const uint32_t k_reset = static_cast<uint32_t>(ceil_div(B, cfg->R_reset));
+  const bool reset_now = cfg->H > 0 && t % cfg->H == 0;
+  uint8_t* mask_step = masks;
+  uint8_t* mask_reset = masks + CSER_STATIC_MAX_BLOCKS;
+  // every byte of a mask is written by the selector (a fill kernel, then the exceptions), so what an earlier
+  // call left in the array does not matter
+  CSER_HIP(cser::launch_selector(cfg->seed, 0u, t, 0u, 1u, static_cast<uint32_t>(B), k_step, mask_step, nullptr, s));
+  if (reset_now)
+    CSER_HIP(cser::launch_selector(cfg->seed, 1u, t, 0u, 1u, static_cast<uint32_t>(B), k_reset, mask_reset, nullptr, s));
+  cser::StepParams p;
+  p.g = g;
+  p.m = m;
+  p.x = x;
+  p.e = e;
+  p.mask = mask_step;
+  p.reset_mask = reset_now ? mask_reset : nullptr;   // the error reset is carried out in the same kernel pass
+  p.ld = cfg->ld;
+  p.d = cfg->d;
+  p.W = cfg->W;
+  p.block = cfg->block;
+  p.eta = cfg->lr;
+  p.beta = cfg->momentum;
+  CSER_HIP(cser::launch_step(p, cfg->block % 4 == 0, nontemporal, cser::Tuning(), caps,
+                             sync_share(B, k_step, k_reset, reset_now), nullptr, s));
+  return CSER_OK;
+}
 
 // ---------------------------------------------------------------- measurement only (cser_measure.h)
 
