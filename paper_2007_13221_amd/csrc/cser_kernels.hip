@@ -118,7 +118,7 @@ __device__ __forceinline__ Pack<V> local_update(float eta, float beta, const Pac
 //      ebar = ordered sum of the post-step e_j / W, x_j <- (x_j - e_j) + ebar, e_j <- +0
 //      (implementation II: x_j <- ordered sum of the post-step x_j / W).
 // Every workgroup of a tile thus does its share of the tile's synchronised work whatever part of the blocks is
-// chosen, and each value is read and written exactly once.  Workgroup id -> (worker, tile) with tiles fastest:
+// chosen, and each value is read and written exactly once.  Grid (tiles, W), dispatched with tiles fastest:
 // the resident wavefronts sweep one worker's row through seven linear streams.
 // ==========================================================================================
 
@@ -138,21 +138,23 @@ __device__ __forceinline__ Pack<4> worker_sum_in_wave(const Pack<4>& v, uint32_t
 }
 
 template <bool NT, bool HAS_E, bool HAS_M>
-__global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32_t groups, uint32_t tiles) {
-  const uint32_t i = blockIdx.x / tiles, tile = blockIdx.x - i * tiles;
+__global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32_t groups) {
+  const uint32_t i = blockIdx.y, tile = blockIdx.x;   // workgroups are dispatched with x fastest: tiles of one worker's row
   const uint32_t lane = threadIdx.x;
-  const uint32_t groups_per_block = a.block / 4u;
-  const uint32_t G = 64u / a.W;                    // column groups per slice
-  const uint32_t j = lane / G, k = lane - j * G;   // role B: worker j, group k of the slice
-  const uint32_t slices = (64u + G - 1u) / G;      // W when W divides 64, up to 2 W - 1 otherwise
   const uint64_t tile_first = static_cast<uint64_t>(tile) * 64u;
-  const float n = static_cast<float>(a.W);
 
-  // role A
+  // Lane l looks up the two choices for column group l of the tile; the ballots hand every lane the choices of
+  // all 64 groups (bit l = group l), so role B below needs no second look-up, and a tile that neither compressor
+  // touches -- the common case -- is recognised at once.
   const uint64_t qa = tile_first + lane;
   const bool live_a = qa < groups;
-  const uint32_t ba = static_cast<uint32_t>(live_a ? qa : 0u) / groups_per_block;
-  const bool local_a = live_a && a.mask[ba] == 0 && (a.reset_mask == nullptr || a.reset_mask[ba] == 0);
+  const uint32_t ba = static_cast<uint32_t>(live_a ? qa : 0u) / (a.block / 4u);
+  const bool step_a = live_a && a.mask[ba] != 0;
+  const bool reset_a = live_a && a.reset_mask != nullptr && a.reset_mask[ba] != 0;
+  const uint64_t step_bits = __ballot(step_a), reset_bits = __ballot(reset_a);
+
+  // role A
+  const bool local_a = live_a && !step_a && !reset_a;
   const uint64_t off_a = static_cast<uint64_t>(i) * a.ld + qa * 4u;
   Pack<4> ga, ma, xa, ea;
   if (local_a) {
@@ -161,27 +163,8 @@ __global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32
     xa = load_pack<4, NT>(a.x + off_a);
     if constexpr (HAS_E) ea = load_pack<4, NT>(a.e + off_a);
   }
-
-  for (uint32_t slice = i; slice < slices; slice += a.W) {   // runs once when W divides 64, else once or twice
-    // role B
-    const uint32_t within = slice * G + k;
-    const uint64_t qb = tile_first + within;
-    const bool live_b = j < a.W && within < 64u && qb < groups;
-    const uint32_t bb = static_cast<uint32_t>(live_b ? qb : 0u) / groups_per_block;
-    const bool step_b = live_b && a.mask[bb] != 0;
-    const bool reset_b = live_b && a.reset_mask != nullptr && a.reset_mask[bb] != 0;
-    const bool sync_b = step_b || reset_b;
-    const uint64_t off_b = static_cast<uint64_t>(j) * a.ld + qb * 4u;
-    Pack<4> gb = zero_pack<4>(), mb = zero_pack<4>(), xb = zero_pack<4>(), eb = zero_pack<4>();
-    if (sync_b) {
-      gb = load_pack<4, NT>(a.g + off_b);
-      if constexpr (HAS_M) mb = load_pack<4, NT>(a.m + off_b);
-      xb = load_pack<4, NT>(a.x + off_b);
-      if constexpr (HAS_E) {
-        if (reset_b) eb = load_pack<4, NT>(a.e + off_b);   // e is untouched by the step on a block C_step chose
-      }
-    }
-    if (slice == i && local_a) {   // role A's arithmetic, once its loads and role B's are all in flight
+  auto finish_role_a = [&]() {
+    if (local_a) {
       const Pack<4> p = local_update<4, HAS_M>(a.eta, a.beta, ga, ma);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
@@ -192,6 +175,34 @@ __global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32
       store_pack<4, NT>(a.x + off_a, xa);
       if constexpr (HAS_E) store_pack<4, NT>(a.e + off_a, ea);
     }
+  };
+  if ((step_bits | reset_bits) == 0) {   // wavefront-uniform
+    finish_role_a();
+    return;
+  }
+
+  // role B
+  const uint32_t G = 64u / a.W;                    // column groups per slice
+  const uint32_t j = lane / G, k = lane - j * G;   // worker j, group k of the slice
+  const uint32_t slices = (64u + G - 1u) / G;      // W when W divides 64, up to 2 W - 1 otherwise
+  const float n = static_cast<float>(a.W);
+  for (uint32_t slice = i; slice < slices; slice += a.W) {   // runs once when W divides 64, else once or twice
+    const uint32_t within = slice * G + k;
+    const bool lane_b = j < a.W && within < 64u;
+    const bool step_b = lane_b && ((step_bits >> (within & 63u)) & 1u) != 0;
+    const bool reset_b = lane_b && ((reset_bits >> (within & 63u)) & 1u) != 0;
+    const bool sync_b = step_b || reset_b;
+    const uint64_t off_b = static_cast<uint64_t>(j) * a.ld + (tile_first + within) * 4u;
+    Pack<4> gb = zero_pack<4>(), mb = zero_pack<4>(), xb = zero_pack<4>(), eb = zero_pack<4>();
+    if (sync_b) {
+      gb = load_pack<4, NT>(a.g + off_b);
+      if constexpr (HAS_M) mb = load_pack<4, NT>(a.m + off_b);
+      xb = load_pack<4, NT>(a.x + off_b);
+      if constexpr (HAS_E) {
+        if (reset_b) eb = load_pack<4, NT>(a.e + off_b);   // e is untouched by the step on a block C_step chose
+      }
+    }
+    if (slice == i) finish_role_a();   // role A's arithmetic, once its loads and role B's are all in flight
     if (__any(sync_b)) {   // wavefront-uniform: all 64 lanes take part in the shuffles below
       Pack<4> p = zero_pack<4>();
       if (sync_b) {
@@ -785,13 +796,11 @@ hipError_t launch_general(const StepParams& p, uint64_t col_begin, uint64_t col_
 
 hipError_t launch_tile(const StepParams& p, uint32_t groups, bool nt, uint32_t lds, hipStream_t s) {
   const uint64_t tiles64 = (static_cast<uint64_t>(groups) + 63) / 64;
-  const uint64_t grid64 = tiles64 * p.W;
-  if (grid64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;   // the C ABI rejects such sizes at create
-  const uint32_t tiles = static_cast<uint32_t>(tiles64);
-  const dim3 grid(static_cast<uint32_t>(grid64)), block(64);
+  if (tiles64 * p.W > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;   // the C ABI rejects such sizes at create
+  const dim3 grid(static_cast<uint32_t>(tiles64), p.W), block(64);
   return with_flags(nt, p.e != nullptr, p.m != nullptr, [&](auto NT, auto E, auto M) {
     hipLaunchKernelGGL((cser_step_tile_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>), grid, block, lds, s,
-                       p, groups, tiles);
+                       p, groups);
     return hipGetLastError();
   });
 }
@@ -845,17 +854,17 @@ hipError_t cap_by_lds(const void* fn, uint32_t threads, uint32_t needed, uint32_
 
 }  // namespace
 
-// Residency: measured on the large workload, the one-wavefront kernel is fastest with about 20 resident
-// wavefronts per CU when a wavefront has 4 load streams (g, m, x, e), 22 with 3, uncapped with 2 (each is the best
-// or within 0.5 % of the best of a sweep, and 4-19 % better than the wrong one; below 14 it falls off steeply);
-// the LDS-shared kernels with about 24 wavefronts per CU.
+// Residency: measured on the large workload at R_step 256, 4 and 2, the one-wavefront kernel is fastest with 14-20
+// resident wavefronts per CU when a wavefront has 4 load streams (g, m, x, e; uncapped, 28 fit and it is 5 % slower),
+// 16-20 with 3, uncapped with 2 (there a cap of 20 costs 4-14 %); the LDS-shared kernels with about 24 wavefronts
+// per CU.
 hipError_t resolve_caps(uint32_t W, bool has_e, bool has_m, bool nontemporal, const Tuning& tune, Caps* out) {
   *out = Caps();
   hipError_t err = hipSuccess;
   if (W <= 64) {
     const int streams = 2 + (has_e ? 1 : 0) + (has_m ? 1 : 0);
     const uint32_t want = tune.tile_waves_per_cu >= 0 ? static_cast<uint32_t>(tune.tile_waves_per_cu)
-                                                      : (streams >= 4 ? 20u : (streams == 3 ? 22u : 0u));
+                                                      : (streams >= 4 ? 16u : (streams == 3 ? 18u : 0u));
     const void* fn = with_flags(nontemporal, has_e, has_m, [](auto NT, auto E, auto M) {
       return reinterpret_cast<const void*>(&cser_step_tile_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>);
     });

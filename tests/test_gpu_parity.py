@@ -455,7 +455,7 @@ def test_residency_caps_are_what_the_launches_get():
     """The kernels bound the wavefronts resident on a CU by the size of their dynamic LDS request; the request is
     chosen with the runtime's occupancy calculator, and what it reports for the chosen request is the cap asked for."""
     dev = torch.device("cuda:0")
-    for with_error, with_momentum, want_tile in ((True, True, 20), (False, True, 22), (True, False, 22), (False, False, None)):
+    for with_error, with_momentum, want_tile in ((True, True, 16), (False, True, 18), (True, False, 18), (False, False, None)):
         wl = _wl(d=100000, W=8, momentum=0.9 if with_momentum else 0.0)
         cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
         opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=with_error, with_momentum=with_momentum)
