@@ -112,7 +112,7 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
     opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=variant_e, with_momentum=variant_m)
     for item in tune:
         key, value = item.split("=")
-        B.cser_set_tuning(opt.ctx, TUNING_KEYS.get(key, key if not key.isdigit() else int(key)), int(value))
+        B.cser_set_tuning(opt.ctx, TUNING_KEYS[key], int(value))
     grads = [I.gradient(wl, t, dev) for t in (1, 2)]   # generated outside every timed region
     stream = torch.cuda.current_stream().cuda_stream
     glist = B.gradient_list([grads[t & 1] for t in range(steps)])
@@ -227,6 +227,52 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
     return out
 
 
+def run_explicit_resets(wl, reps, tune=(), variant_e=True):
+    """Time cser_error_reset (block selection, ordered block list, reset kernel) `reps` times at t = 1, 2, ...: the
+    blocks differ from call to call.  States hold random values; nothing is stepped."""
+    import torch
+    from paper_2007_13221_amd import binding as B
+    from paper_2007_13221_amd import inputs as I
+
+    dev = torch.device("cuda:0")
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=variant_e)
+    for item in tune:
+        key, value = item.split("=")
+        B.cser_set_tuning(opt.ctx, TUNING_KEYS[key], int(value))
+    if variant_e:
+        opt.e.normal_(0.0, 0.01)
+    torch.cuda.synchronize()
+    B.cser_set_step(opt.ctx, 0)
+    opt.error_reset()
+    torch.cuda.synchronize()
+    B.cser_profile_enable(opt.ctx, True)
+    B.cser_profile_clear(opt.ctx)
+    stream = torch.cuda.current_stream().cuda_stream
+    t0 = time.perf_counter()
+    for r in range(reps):
+        B.cser_set_step(opt.ctx, r + 1)
+        B.cser_error_reset(opt.ctx, stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms, n = B.cser_profile_read(opt.ctx, 1)
+    total = 0
+    for r in range(reps):
+        _, mask = B.cser_select_blocks(opt.ctx, 1, r + 1)
+        total += reset_bytes(wl, chosen_columns(wl, mask), variant_e)
+    per = total / reps
+    kernel_ms = ms / max(n, 1)
+    gbps = per / (kernel_ms * 1e-3) / 1e9
+    out = {"mode": "explicit error resets (cser_error_reset)", "workload": f"{wl.name}: d={wl.d}, W={wl.W}, block={wl.block}, R_reset={wl.R_reset}",
+           "resets": reps, "ms_per_call": elapsed * 1e3 / reps,
+           "roofline": {"bound": "hbm", "kernel": "cser_reset_shared_kernel" if wl.W <= 16 and wl.block % 4 == 0 else "cser_reset_general_kernel",
+                        "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                        "bytes_per_launch": per, "ms_per_launch": kernel_ms, "launches": n},
+           "whole_call_GBps": total / elapsed / 1e9}
+    opt.close()
+    return out
+
+
 def compact(wl, r):
     return {"workload": wl.name, "R_step": wl.R_step, "R_reset": wl.R_reset, "block": wl.block, "H": wl.H,
             "steps": r["steps"], "ms_per_step": round(r["ms_per_step"], 4),
@@ -257,6 +303,11 @@ def main():
     ap.add_argument("--table4", action="store_true",
                     help="one compact line per CSER row of the paper's Table 4 (compressor pair and reset interval for "
                          "each overall ratio) at the large-CNN size, max(64, 2 H) steps each")
+    ap.add_argument("--workers", type=int, default=0, help="override the workload's number of workers W")
+    ap.add_argument("--override", action="append", default=[], metavar="FIELD=VALUE",
+                    help="override an integer field of the workload (R_step, R_reset, H, block), e.g. R_step=1")
+    ap.add_argument("--explicit-resets", type=int, default=0, metavar="N",
+                    help="instead of stepping: time N calls of cser_error_reset on the workload")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
                     help="cser_set_tuning(key, value) before the run (launch-shape experiments); keys: " + ", ".join(TUNING_KEYS))
     args = ap.parse_args()
@@ -282,6 +333,17 @@ def main():
     named.update({w.name: w for w in I.sweep_workloads()})
     named.update({w.name: w for w in I.table4_workloads()})
     wl = named[args.workload]
+    from dataclasses import replace
+    if args.workers:
+        wl = replace(wl, W=args.workers, name=f"{wl.name}_W{args.workers}")
+    for item in args.override:
+        field, value = item.split("=")
+        if field not in ("R_step", "R_reset", "H", "block"):
+            sys.exit(f"bench.py: cannot override {field}")
+        wl = replace(wl, **{field: int(value)}, name=f"{wl.name}_{field}{value}")
+    if args.explicit_resets:
+        print(json.dumps(run_explicit_resets(wl, args.explicit_resets, args.tune, variant_e)))
+        return
     out = run_workload(wl, args.steps, args.warmup, args.tune, variant_e=variant_e, variant_m=variant_m)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, variant_e, variant_m)

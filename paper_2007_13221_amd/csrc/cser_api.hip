@@ -88,6 +88,7 @@ struct cser_ctx {
   uint64_t win_reset_t0;     // first reset iteration (multiple of H) in the window
   uint32_t win_reset_n;      // number of reset iterations in the window
   uint32_t* idx_reset;       // device, max(k_reset, 1) entries: the reset's block list in increasing order
+  uint32_t* list_counts;     // device scratch of the ordered-list kernels
   uint8_t* mask_query;       // device scratch of cser_select_blocks, B bytes
   uint32_t* idx_query;       // device scratch of cser_select_blocks, max(k_step, k_reset, 1) entries
   hipStream_t query_stream;  // cser_select_blocks runs here
@@ -146,6 +147,7 @@ void free_device_arrays(cser_ctx* ctx) {
   if (ctx->mask_reset_win) (void)hipFree(ctx->mask_reset_win);
   if (ctx->win_done) (void)hipEventDestroy(ctx->win_done);
   if (ctx->idx_reset) (void)hipFree(ctx->idx_reset);
+  if (ctx->list_counts) (void)hipFree(ctx->list_counts);
   if (ctx->mask_query) (void)hipFree(ctx->mask_query);
   if (ctx->idx_query) (void)hipFree(ctx->idx_query);
   if (ctx->query_stream) (void)hipStreamDestroy(ctx->query_stream);
@@ -258,6 +260,8 @@ int cser_create(const cser_config* cfg, float* x, float* e, float* m, void* hip_
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->mask_query), ctx->B);
   if (err == hipSuccess)
     err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_reset), sizeof(uint32_t) * (ctx->k_reset ? ctx->k_reset : 1u));
+  if (err == hipSuccess)
+    err = hipMalloc(reinterpret_cast<void**>(&ctx->list_counts), sizeof(uint32_t) * cser::kOrderedListCounts);
   if (err == hipSuccess) err = hipMalloc(reinterpret_cast<void**>(&ctx->idx_query), sizeof(uint32_t) * (k_max ? k_max : 1u));
   if (err == hipSuccess) err = hipStreamCreateWithFlags(&ctx->query_stream, hipStreamNonBlocking);
   if (err != hipSuccess) {
@@ -293,7 +297,8 @@ int cser_error_reset(cser_ctx* ctx, void* hip_stream) {
   // the mask from the blocks' side, then the chosen ids in increasing order: the kernel sweeps the rows forwards
   CSER_HIP(cser::launch_selector(ctx->cfg.seed, 1u, ctx->t, 0u, 1u, static_cast<uint32_t>(ctx->B), ctx->k_reset,
                                  ctx->mask_reset, nullptr, s));
-  CSER_HIP(cser::launch_ordered_list(ctx->mask_reset, static_cast<uint32_t>(ctx->B), ctx->k_reset, ctx->idx_reset, s));
+  CSER_HIP(cser::launch_ordered_list(ctx->mask_reset, static_cast<uint32_t>(ctx->B), ctx->k_reset, ctx->list_counts,
+                                     ctx->idx_reset, s));
   cser::ResetParams p;
   p.x = ctx->x;
   p.e = ctx->e;

@@ -70,8 +70,11 @@ hipError_t resolve_caps(uint32_t W, bool has_e, bool has_m, bool nontemporal, co
 hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint64_t t_stride, uint32_t count, uint32_t B,
                            uint32_t k, uint8_t* mask, uint32_t* idx, hipStream_t s);
 
-// The chosen block ids of a mask (which holds exactly k of them) in increasing order: idx_sorted[0..k).
-hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* idx_sorted, hipStream_t s);
+// The chosen block ids of a mask (16-byte aligned, holding exactly k of them) in increasing order: idx_sorted[0..k).
+// counts: device scratch of kOrderedListCounts entries.
+constexpr uint32_t kOrderedListCounts = 1024;
+hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* counts, uint32_t* idx_sorted,
+                               hipStream_t s);
 
 // Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d) (and the error reset when p.reset_mask is set).
 // `vectorised` requires block to be a multiple of 4 columns (rows need only 4-byte alignment).  `sync_share`:

@@ -2,7 +2,8 @@
 //
 //   grbs_select_kernel        the shared-seed block choice of the GRBS compressor (Definition 2, Section 3.3),
 //   grbs_scatter_kernel       from the blocks' side (inverse permutation) or from the draws' side (forward)
-//   ordered_list_kernel       the chosen block ids of a mask in increasing order (for the reset kernel)
+//   count_chosen_kernel,      the chosen block ids of a mask in increasing order (for the reset kernel)
+//   ordered_list_kernel
 //   cser_step_tile_kernel     Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass, and on reset
 //                             iterations the error reset as well; one-wavefront workgroups, W <= 64: the default
 //   cser_step_shared_kernel   the same with W-wavefront workgroups and the worker sums staged in LDS (W <= 16);
@@ -719,27 +720,63 @@ __global__ __launch_bounds__(256) void grbs_scatter_kernel(uint32_t seed_lo, uin
   }
 }
 
-// The block ids b with mask[b] != 0 in increasing order, out[0 .. k).  One workgroup of 1024 lanes: each lane
-// counts the chosen blocks of its contiguous share of the mask, an inclusive scan over the 1024 counts gives
-// every lane the position of its first entry, and a second walk over the share writes the ids.  `k` bounds the
-// writes (the mask holds exactly k chosen blocks by construction).
-__global__ __launch_bounds__(1024) void ordered_list_kernel(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* out) {
-  __shared__ uint32_t counts[1024];
-  const uint32_t tid = threadIdx.x;
-  const uint64_t per = (static_cast<uint64_t>(B) + 1023u) / 1024u;
-  const uint64_t b0 = tid * per < B ? tid * per : B;
-  const uint64_t b1 = b0 + per < B ? b0 + per : B;
+// The block ids b with mask[b] != 0 in increasing order, out[0 .. k): two launches over the same decomposition.
+// The mask is cut into chunks of `chunk` bytes (a multiple of 4096, at most 1024 chunks), one workgroup of 256
+// lanes per chunk, each lane owning chunk / 256 consecutive bytes.  count_chosen_kernel writes the number of
+// chosen blocks of every chunk; ordered_list_kernel adds up the counts of the chunks before its own, scans its
+// lanes' counts and writes the ids.  `k` bounds the writes (the mask holds exactly k chosen blocks by construction).
+__device__ __forceinline__ uint32_t count_nonzero_bytes(const uint8_t* mask, uint64_t begin, uint64_t end) {
   uint32_t c = 0;
-  for (uint64_t b = b0; b < b1; ++b) c += mask[b] != 0 ? 1u : 0u;
-  counts[tid] = c;
+  uint64_t b = begin;
+  for (; b + 16 <= end; b += 16) {   // begin is a multiple of 16 and the mask is 16-byte aligned
+    const uint4 w = *reinterpret_cast<const uint4*>(mask + b);
+    const uint32_t words[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int s = 0; s < 32; s += 8) c += ((words[i] >> s) & 0xFFu) != 0 ? 1u : 0u;
+    }
+  }
+  for (; b < end; ++b) c += mask[b] != 0 ? 1u : 0u;
+  return c;
+}
+
+__device__ __forceinline__ uint32_t workgroup_inclusive_scan_256(uint32_t value, uint32_t* shared) {
+  const uint32_t tid = threadIdx.x;
+  shared[tid] = value;
   __syncthreads();
-  for (uint32_t step = 1; step < 1024u; step <<= 1) {
-    const uint32_t add = tid >= step ? counts[tid - step] : 0u;
+  for (uint32_t step = 1; step < 256u; step <<= 1) {
+    const uint32_t add = tid >= step ? shared[tid - step] : 0u;
     __syncthreads();
-    counts[tid] += add;
+    shared[tid] += add;
     __syncthreads();
   }
-  uint32_t pos = counts[tid] - c;
+  return shared[tid];
+}
+
+__global__ __launch_bounds__(256) void count_chosen_kernel(const uint8_t* mask, uint32_t B, uint32_t chunk, uint32_t* counts) {
+  __shared__ uint32_t shared[256];
+  const uint64_t per = chunk / 256u;
+  const uint64_t begin = static_cast<uint64_t>(blockIdx.x) * chunk + threadIdx.x * per;
+  const uint64_t b0 = begin < B ? begin : B, b1 = begin + per < B ? begin + per : B;
+  const uint32_t total = workgroup_inclusive_scan_256(count_nonzero_bytes(mask, b0, b1), shared);
+  if (threadIdx.x == 255u) counts[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void ordered_list_kernel(const uint8_t* mask, uint32_t B, uint32_t chunk, const uint32_t* counts,
+                                                            uint32_t k, uint32_t* out) {
+  __shared__ uint32_t shared[256];
+  const uint32_t tid = threadIdx.x;
+  uint32_t before = 0;   // chosen blocks in the chunks before this one: every lane adds up a stride of the counts
+  for (uint32_t c = tid; c < blockIdx.x; c += 256u) before += counts[c];
+  (void)workgroup_inclusive_scan_256(before, shared);   // leaves the total in shared[255]
+  const uint32_t chunk_base = shared[255];
+  __syncthreads();                                       // everyone has read it before `shared` is used again
+  const uint64_t per = chunk / 256u;
+  const uint64_t begin = static_cast<uint64_t>(blockIdx.x) * chunk + tid * per;
+  const uint64_t b0 = begin < B ? begin : B, b1 = begin + per < B ? begin + per : B;
+  const uint32_t mine = count_nonzero_bytes(mask, b0, b1);
+  uint32_t pos = chunk_base + workgroup_inclusive_scan_256(mine, shared) - mine;
   for (uint64_t b = b0; b < b1; ++b) {
     if (mask[b] != 0 && pos < k) out[pos++] = static_cast<uint32_t>(b);
   }
@@ -917,9 +954,21 @@ hipError_t launch_selector(uint64_t seed, uint32_t stream_id, uint64_t t0, uint6
   return hipGetLastError();
 }
 
-hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* idx_sorted, hipStream_t s) {
+uint32_t ordered_list_chunk(uint32_t B) {
+  uint64_t chunk = 4096;   // bytes of the mask per workgroup: at most 1024 workgroups
+  while ((static_cast<uint64_t>(B) + chunk - 1) / chunk > 1024) chunk *= 2;
+  return static_cast<uint32_t>(chunk);
+}
+
+hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* counts, uint32_t* idx_sorted,
+                               hipStream_t s) {
   if (k == 0) return hipSuccess;
-  hipLaunchKernelGGL(ordered_list_kernel, dim3(1), dim3(1024), 0, s, mask, B, k, idx_sorted);
+  const uint32_t chunk = ordered_list_chunk(B);
+  const dim3 grid(static_cast<uint32_t>((static_cast<uint64_t>(B) + chunk - 1) / chunk)), block(256);
+  hipLaunchKernelGGL(count_chosen_kernel, grid, block, 0, s, mask, B, chunk, counts);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(ordered_list_kernel, grid, block, 0, s, mask, B, chunk, counts, k, idx_sorted);
   return hipGetLastError();
 }
 
@@ -931,9 +980,12 @@ hipError_t launch_step(const StepParams& p, bool vectorised, bool nontemporal, c
     if (kernel == kKernelTile && p.W > 64) kernel = kKernelAuto;
     if (kernel == kKernelShared && p.W > 16) kernel = kKernelAuto;
     if (kernel == kKernelAuto) {
-      // the LDS-shared kernel moves the synchronised blocks' bytes faster and the others' slower than the
-      // one-wavefront kernel; measured break-even at somewhat more than half of the blocks
-      if (p.W <= 16 && sync_share >= 0.55) kernel = kKernelShared;
+      // The LDS-shared kernel moves the synchronised blocks' bytes faster (6.0 TB/s whatever W) and the others'
+      // slower (5.7-6.0 against 6.5) than the one-wavefront kernel, whose synchronised path reads 64 / W column
+      // groups per worker at a time: 5 TB/s at W = 8, 1.6-3.1 at W = 3, 6, 12, 16.  Measured break-even: half of the
+      // blocks for W = 1, 2, 4, 8, a tenth otherwise.
+      const bool wide_runs = p.W == 1 || p.W == 2 || p.W == 4 || p.W == 8;
+      if (p.W <= 16 && sync_share >= (wide_runs ? 0.5 : 0.1)) kernel = kKernelShared;
       else if (p.W <= 64) kernel = kKernelTile;
       else kernel = kKernelGeneral;
     }
