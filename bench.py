@@ -27,7 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, vendor figure
 TUNING_KEYS = {"kernel": 0, "nontemporal": 1, "fuse_reset": 2, "tile_waves_per_cu": 3, "shared_groups_per_cu": 4}
 KERNEL_NAMES = {"launches_tile": "cser_step_tile_kernel", "launches_shared": "cser_step_shared_kernel",
-                "launches_general": "cser_step_general_kernel"}
+                "launches_general": "cser_step_general_kernel",
+                "launches_split": "cser_step_tile_kernel+cser_step_shared_kernel"}
 
 
 def step_bytes(wl, d_sel, with_error=True, with_momentum=True):

@@ -26,7 +26,8 @@ int cser_profile_clear(cser_ctx* ctx);
 typedef enum cser_tuning_key {
   CSER_TUNE_KERNEL = 0,            /* 0 (default) automatic; 1 one-wavefront workgroups, a worker's row each (W <= 64);
                                       2 W-wavefront workgroups, worker sums staged in LDS (W <= 16); 3 a lane walks all
-                                      workers (any W).  A kernel that does not take the context's W falls back to 0. */
+                                      workers (any W); 4 a pair of launches, 1 on the blocks neither compressor chose and
+                                      2 on the others (W <= 16).  A kernel that does not take the context's W falls back to 0. */
   CSER_TUNE_NONTEMPORAL = 1,       /* -1 (default) non-temporal accesses unless all state fits 256 MiB; 0 never; 1 always */
   CSER_TUNE_FUSE_RESET = 2,        /* 1 (default) on iterations with t mod H = 0 the error reset runs inside the fused-step
                                       kernel (x and e of its blocks make one trip instead of two); 0 separate reset kernel */
@@ -43,9 +44,10 @@ typedef struct cser_counters {
   uint64_t window_draws;      /* times the masks of the next iterations were drawn (selector launches)   */
   uint64_t resets_fused;      /* error resets carried out inside the fused-step kernel                   */
   uint64_t resets_separate;   /* error resets carried out by the reset kernel                            */
-  uint64_t launches_tile;     /* fused-step launches by kernel                                           */
+  uint64_t launches_tile;     /* fused steps by kernel choice (1, 2, 3, 4 of CSER_TUNE_KERNEL)           */
   uint64_t launches_shared;
   uint64_t launches_general;
+  uint64_t launches_split;
 } cser_counters;
 int cser_measure_counters(const cser_ctx* ctx, cser_counters* out);
 

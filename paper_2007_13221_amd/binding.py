@@ -25,7 +25,7 @@ MEASURE_EXPORTS = ("cser_profile_enable", "cser_profile_read", "cser_profile_cle
 # cser_tuning_key
 CSER_TUNE_KERNEL, CSER_TUNE_NONTEMPORAL, CSER_TUNE_FUSE_RESET = 0, 1, 2
 CSER_TUNE_TILE_WAVES_PER_CU, CSER_TUNE_SHARED_GROUPS_PER_CU = 3, 4
-KERNEL_AUTO, KERNEL_TILE, KERNEL_SHARED, KERNEL_GENERAL = 0, 1, 2, 3
+KERNEL_AUTO, KERNEL_TILE, KERNEL_SHARED, KERNEL_GENERAL, KERNEL_SPLIT = 0, 1, 2, 3, 4
 
 
 class cser_config(ctypes.Structure):
@@ -37,7 +37,8 @@ class cser_config(ctypes.Structure):
 
 class cser_counters(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in ("steps", "window_draws", "resets_fused", "resets_separate",
-                                               "launches_tile", "launches_shared", "launches_general")]
+                                               "launches_tile", "launches_shared", "launches_general",
+                                               "launches_split")]
 
 
 class cser_residency(ctypes.Structure):

@@ -355,6 +355,7 @@ int cser_step(cser_ctx* ctx, const float* g, void* hip_stream) {
   ctx->counters.steps += 1;
   if (used == cser::kKernelTile) ctx->counters.launches_tile += 1;
   else if (used == cser::kKernelShared) ctx->counters.launches_shared += 1;
+  else if (used == cser::kKernelSplit) ctx->counters.launches_split += 1;
   else ctx->counters.launches_general += 1;
   if (fused) ctx->counters.resets_fused += 1;
   if (reset_now && !fused) return cser_error_reset(ctx, hip_stream);
@@ -587,7 +588,7 @@ int cser_set_tuning(cser_ctx* ctx, int key, int64_t value) {
   cser::Tuning next = ctx->tuning;
   switch (key) {
     case CSER_TUNE_KERNEL:
-      if (value < 0 || value > 3) return CSER_EINVAL;
+      if (value < 0 || value > 4) return CSER_EINVAL;
       next.kernel = static_cast<int>(value);
       break;
     case CSER_TUNE_NONTEMPORAL:

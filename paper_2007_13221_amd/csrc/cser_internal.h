@@ -23,6 +23,14 @@ struct StepParams {
   uint32_t block;
   float eta;
   float beta;
+  uint32_t part;              // kPartAll, or one half of a launch pair (see kKernelSplit)
+};
+
+// Which column groups a fused-step launch works on.
+enum StepPart : uint32_t {
+  kPartAll = 0,
+  kPartLocal = 1,          // only those in blocks neither compressor chose at this t
+  kPartSynchronised = 2    // only those in blocks C_step (or, with a fused reset, C_reset) chose
 };
 
 struct ResetParams {
@@ -41,7 +49,8 @@ enum StepKernel {
   kKernelAuto = 0,     // by worker count and by the share of blocks that need the worker mean this iteration
   kKernelTile = 1,     // one-wavefront workgroups, one worker's row per workgroup (W <= 64)
   kKernelShared = 2,   // W-wavefront workgroups, worker sums staged in LDS (W <= 16)
-  kKernelGeneral = 3   // a lane walks all workers (any W, any block size)
+  kKernelGeneral = 3,  // a lane walks all workers (any W, any block size)
+  kKernelSplit = 4     // two launches: kKernelTile on the blocks neither compressor chose, kKernelShared on the others (W <= 16)
 };
 
 struct Tuning {

@@ -177,7 +177,7 @@ __global__ __launch_bounds__(64) void cser_step_tile_kernel(StepParams a, uint32
       if constexpr (HAS_E) store_pack<4, NT>(a.e + off_a, ea);
     }
   };
-  if ((step_bits | reset_bits) == 0) {   // wavefront-uniform
+  if ((step_bits | reset_bits) == 0 || a.part == kPartLocal) {   // wavefront-uniform
     finish_role_a();
     return;
   }
@@ -293,10 +293,16 @@ __global__ __launch_bounds__(1024) void cser_step_shared_kernel(StepParams a, ui
   extern __shared__ f4 stage[];
   const uint32_t lane = threadIdx.x & 63u, i = threadIdx.x >> 6;
   const uint64_t q = static_cast<uint64_t>(blockIdx.x) * 64u + lane;
-  const bool live = q < groups;
+  bool live = q < groups;
   const uint32_t b = static_cast<uint32_t>(live ? q : 0u) / (a.block / 4u);
   const bool step_c = live && a.mask[b] != 0;
   const bool reset_c = live && a.reset_mask != nullptr && a.reset_mask[b] != 0;
+  if (a.part == kPartSynchronised) {
+    // the blocks neither compressor chose have been updated by the one-wavefront kernel.  The masks are the same
+    // for every wavefront of the workgroup, so either all of them leave here or none does.
+    live = live && (step_c || reset_c);
+    if (!__any(live)) return;
+  }
   const bool touches_e = HAS_E && live && (!step_c || reset_c);   // e is untouched by the step on a block C_step chose
   const uint64_t off = static_cast<uint64_t>(i) * a.ld + q * 4u;
   Pack<4> g = zero_pack<4>(), m = zero_pack<4>(), x = zero_pack<4>(), e = zero_pack<4>();
@@ -972,20 +978,29 @@ hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint
   return hipGetLastError();
 }
 
-hipError_t launch_step(const StepParams& p, bool vectorised, bool nontemporal, const Tuning& tune, const Caps& caps,
+hipError_t launch_step(const StepParams& p_in, bool vectorised, bool nontemporal, const Tuning& tune, const Caps& caps,
                        double sync_share, int* used, hipStream_t s) {
+  StepParams p = p_in;
+  p.part = kPartAll;
   int kernel = kKernelGeneral;
   if (vectorised) {
     kernel = tune.kernel;
     if (kernel == kKernelTile && p.W > 64) kernel = kKernelAuto;
-    if (kernel == kKernelShared && p.W > 16) kernel = kKernelAuto;
+    if ((kernel == kKernelShared || kernel == kKernelSplit) && p.W > 16) kernel = kKernelAuto;
     if (kernel == kKernelAuto) {
-      // The LDS-shared kernel moves the synchronised blocks' bytes faster (6.0 TB/s whatever W) and the others'
-      // slower (5.7-6.0 against 6.5) than the one-wavefront kernel, whose synchronised path reads 64 / W column
-      // groups per worker at a time: 5 TB/s at W = 8, 1.6-3.1 at W = 3, 6, 12, 16.  Measured break-even: half of the
-      // blocks for W = 1, 2, 4, 8, a tenth otherwise.
+      // Three regimes by the share of the blocks that need the worker mean in this launch (measured on the large
+      // workload; algorithmic TB/s of the blocks concerned, W = 8):
+      //   * the one-wavefront kernel sweeps the other blocks at 6.5-6.7 but handles the synchronised ones at 5
+      //     (1.6-3.1 when 64 / W column groups are not a run of 64 bytes or more: W = 3, 6, 12, 16): best while they are few;
+      //   * the LDS-shared kernel moves the synchronised blocks at 6.0-6.3 and the others, W rows at a time from
+      //     one CU, at 5.5-6.0: best when nearly every block is synchronised;
+      //   * in between, each kernel does what it is good at: the one-wavefront kernel takes the blocks neither
+      //     compressor chose, then the LDS-shared kernel the others.  Its workgroups that find nothing to do cost
+      //     about 50 us per 100,000 tiles, which sets the lower end of the range.
+      // Break-even points measured for W = 3, 6, 8, 12, 16 at R_step = 2 .. 256.
       const bool wide_runs = p.W == 1 || p.W == 2 || p.W == 4 || p.W == 8;
-      if (p.W <= 16 && sync_share >= (wide_runs ? 0.5 : 0.1)) kernel = kKernelShared;
+      if (p.W <= 16 && sync_share >= 0.9) kernel = kKernelShared;
+      else if (p.W <= 16 && sync_share >= (wide_runs ? 0.4 : 0.1)) kernel = kKernelSplit;
       else if (p.W <= 64) kernel = kKernelTile;
       else kernel = kKernelGeneral;
     }
@@ -996,10 +1011,20 @@ hipError_t launch_step(const StepParams& p, bool vectorised, bool nontemporal, c
   hipError_t err = hipSuccess;
   if (d4 > 0) {
     const uint32_t groups = static_cast<uint32_t>(d4 / 4);
-    if (kernel == kKernelTile) err = launch_tile(p, groups, nontemporal, caps.tile_lds, s);
-    else if (kernel == kKernelShared)
-      err = launch_shared(p, groups, nontemporal, p.reset_mask != nullptr ? caps.shared_reset_lds : caps.shared_lds, s);
-    else err = launch_general<4>(p, 0, d4, nontemporal, s);
+    const uint32_t shared_lds = p.reset_mask != nullptr ? caps.shared_reset_lds : caps.shared_lds;
+    if (kernel == kKernelTile) {
+      err = launch_tile(p, groups, nontemporal, caps.tile_lds, s);
+    } else if (kernel == kKernelShared) {
+      err = launch_shared(p, groups, nontemporal, shared_lds, s);
+    } else if (kernel == kKernelSplit) {
+      p.part = kPartLocal;
+      err = launch_tile(p, groups, nontemporal, caps.tile_lds, s);
+      p.part = kPartSynchronised;
+      if (err == hipSuccess) err = launch_shared(p, groups, nontemporal, shared_lds, s);
+      p.part = kPartAll;
+    } else {
+      err = launch_general<4>(p, 0, d4, nontemporal, s);
+    }
   }
   if (err != hipSuccess) return err;
   return launch_general<1>(p, d4, p.d, nontemporal, s);   // at most 3 trailing columns

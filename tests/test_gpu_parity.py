@@ -21,7 +21,7 @@ ABS_TOL, REL_TOL = 1e-7, 1e-6
 # launch shapes (measurement interface): every one must give the same bits
 K, NT, FUSE, TILE_CAP, SHARED_CAP = (B.CSER_TUNE_KERNEL, B.CSER_TUNE_NONTEMPORAL, B.CSER_TUNE_FUSE_RESET,
                                      B.CSER_TUNE_TILE_WAVES_PER_CU, B.CSER_TUNE_SHARED_GROUPS_PER_CU)
-TILE, SHARED, GENERAL = B.KERNEL_TILE, B.KERNEL_SHARED, B.KERNEL_GENERAL
+TILE, SHARED, GENERAL, SPLIT = B.KERNEL_TILE, B.KERNEL_SHARED, B.KERNEL_GENERAL, B.KERNEL_SPLIT
 
 
 def assert_states_close(name, got, want):
@@ -114,9 +114,10 @@ def test_selector_indices_and_masks_are_bit_exact(d, block, R_step, R_reset):
 
 # ---------------------------------------------------------------------------- named workloads
 @pytest.mark.parametrize("tuning", [None, {FUSE: 0}, {K: TILE}, {K: SHARED}, {K: SHARED, FUSE: 0}, {K: GENERAL},
-                                    {K: GENERAL, FUSE: 0}],
+                                    {K: GENERAL, FUSE: 0}, {K: SPLIT}, {K: SPLIT, FUSE: 0}],
                          ids=["auto-fused-reset", "auto-separate-reset", "one-wavefront", "lds-shared",
-                              "lds-shared-separate-reset", "lane-walks-workers", "lane-walks-separate"])
+                              "lds-shared-separate-reset", "lane-walks-workers", "lane-walks-separate",
+                              "launch-pair", "launch-pair-separate-reset"])
 def test_tiny_workload_100_steps(tuning):
     wl = I.WORKLOADS["tiny"]
     diff = run_pair(wl, 100, check_every=20, tuning=tuning)
@@ -180,9 +181,9 @@ def test_misaligned_base_pointers():
 
 def test_implementation_two_without_residual_buffer():
     wl = _wl(d=20000, W=8, steps=16)
-    for tuning in (None, {FUSE: 0}, {K: SHARED}, {K: SHARED, FUSE: 0}, {K: GENERAL}):
+    for tuning in (None, {FUSE: 0}, {K: SHARED}, {K: SHARED, FUSE: 0}, {K: GENERAL}, {K: SPLIT}):
         assert run_pair(wl, 16, with_error=False, tuning=tuning) == 0
-    for tuning in (None, {K: SHARED}, {K: GENERAL}):
+    for tuning in (None, {K: SHARED}, {K: GENERAL}, {K: SPLIT}):
         assert run_pair(_wl(d=20000, W=5, R_step=2, R_reset=2, H=1), 8, with_error=False, tuning=tuning) == 0
 
 
@@ -191,13 +192,13 @@ def test_blocks_chosen_by_both_compressors_at_once():
     for kw in (dict(), dict(W=3), dict(block=6), dict(momentum=0.0)):
         wl = _wl(d=30000, R_step=2, R_reset=2, H=1, **kw)
         assert run_pair(wl, 10) == 0
-        for kernel in (TILE, SHARED, GENERAL):
+        for kernel in (TILE, SHARED, GENERAL, SPLIT):
             assert run_pair(wl, 10, tuning={K: kernel}) == 0
 
 
 def test_no_momentum_buffer_is_algorithm_2():
     wl = _wl(d=20000, W=8, momentum=0.0)
-    for tuning in (None, {K: SHARED}, {K: GENERAL}):
+    for tuning in (None, {K: SHARED}, {K: GENERAL}, {K: SPLIT}):
         assert run_pair(wl, 12, with_momentum=False, tuning=tuning) == 0
         assert run_pair(wl, 12, with_momentum=False, with_error=False, tuning=tuning) == 0
 
@@ -205,7 +206,9 @@ def test_no_momentum_buffer_is_algorithm_2():
 @pytest.mark.parametrize("tuning", [{K: TILE}, {K: TILE, NT: 0}, {K: TILE, NT: 1}, {K: TILE, TILE_CAP: 0}, {K: TILE, TILE_CAP: 7},
                                     {K: TILE, FUSE: 0}, {K: SHARED}, {K: SHARED, NT: 0}, {K: SHARED, NT: 1},
                                     {K: SHARED, SHARED_CAP: 0}, {K: SHARED, SHARED_CAP: 1}, {K: SHARED, FUSE: 0},
-                                    {K: GENERAL}, {K: GENERAL, NT: 1}, {K: GENERAL, FUSE: 0}, {NT: 1}, {FUSE: 0}],
+                                    {K: GENERAL}, {K: GENERAL, NT: 1}, {K: GENERAL, FUSE: 0}, {NT: 1}, {FUSE: 0},
+                                    {K: SPLIT}, {K: SPLIT, NT: 0}, {K: SPLIT, NT: 1}, {K: SPLIT, FUSE: 0},
+                                    {K: SPLIT, TILE_CAP: 5, SHARED_CAP: 1}],
                          ids=lambda t: "-".join(f"{k}={v}" for k, v in t.items()))
 def test_results_do_not_depend_on_launch_shape(tuning):
     wl = _wl(d=30000, W=8, steps=8)
@@ -219,7 +222,7 @@ def test_every_worker_count_in_every_kernel_that_takes_it(W, R_step):
     floor(64 / W) groups (two rounds when W does not divide 64); the LDS-shared kernel has W wavefronts per
     workgroup; beyond 64 workers a lane walks the worker axis."""
     wl = _wl(d=2500, W=W, block=8, R_step=R_step, R_reset=2, H=2, steps=4)
-    kernels = [None] + ([TILE] if W <= 64 else []) + ([SHARED] if W <= 16 else []) + [GENERAL]
+    kernels = [None] + ([TILE] if W <= 64 else []) + ([SHARED, SPLIT] if W <= 16 else []) + [GENERAL]
     for kernel in kernels:
         assert run_pair(wl, 4, tuning=None if kernel is None else {K: kernel}) == 0
         assert run_pair(wl, 4, with_error=False, tuning=None if kernel is None else {K: kernel}) == 0
@@ -297,7 +300,7 @@ def _random_cases(n, seed):
             lr=float(rng.choice([0.1, 0.01, 1.0])), seed=int(rng.integers(0, 2**62)),
             ld=int(rng.choice([d, -(-d // 4) * 4, -(-d // 64) * 64, -(-d // 1024) * 1024])),
             with_error=bool(rng.integers(0, 2)), with_momentum=bool(momentum != 0.0 or rng.integers(0, 2)),
-            tuning=[None, {K: GENERAL}, {K: SHARED}, {FUSE: 0}, {K: TILE, NT: 1}, {K: SHARED, NT: 0}, {K: TILE}, None][int(rng.integers(0, 8))]))
+            tuning=[None, {K: GENERAL}, {K: SHARED}, {FUSE: 0}, {K: TILE, NT: 1}, {K: SHARED, NT: 0}, {K: TILE}, {K: SPLIT}][int(rng.integers(0, 8))]))
     return cases
 
 
@@ -427,10 +430,10 @@ def test_profile_timers_counters_and_copy_probe():
     assert B.cser_profile_read(opt.ctx, 0)[1] == 6
     assert B.cser_profile_read(opt.ctx, 1)[1] == 0      # resets ran inside the fused-step kernel
     c = B.cser_measure_counters(opt.ctx)
-    # R_step = 4, R_reset = 2: a quarter of the blocks is synchronised on ordinary iterations (one-wavefront kernel),
-    # five eighths on reset iterations (LDS-shared kernel)
+    # R_step = 4, R_reset = 2: a quarter of the blocks is synchronised on ordinary iterations (one-wavefront kernel), five
+    # eighths on reset iterations (the one-wavefront kernel takes the local blocks, then the LDS-shared kernel the rest)
     assert (c["steps"], c["window_draws"], c["resets_fused"], c["resets_separate"]) == (6, 1, 3, 0)
-    assert (c["launches_tile"], c["launches_shared"], c["launches_general"]) == (3, 3, 0)
+    assert (c["launches_tile"], c["launches_shared"], c["launches_general"], c["launches_split"]) == (3, 0, 0, 3)
     B.cser_profile_clear(opt.ctx)
     B.cser_set_tuning(opt.ctx, FUSE, 0)                  # separate reset kernel
     for _ in range(6):
@@ -440,7 +443,7 @@ def test_profile_timers_counters_and_copy_probe():
     assert n0 == 6 and n1 == 3 and ms0 > 0 and ms1 > 0
     c = B.cser_measure_counters(opt.ctx)
     assert (c["steps"], c["window_draws"], c["resets_fused"], c["resets_separate"]) == (12, 2, 3, 3)
-    assert (c["launches_tile"], c["launches_shared"]) == (9, 3)
+    assert (c["launches_tile"], c["launches_shared"], c["launches_split"]) == (9, 0, 3)
     B.cser_profile_clear(opt.ctx)
     assert B.cser_profile_read(opt.ctx, 0) == (0.0, 0)
     opt.close()
