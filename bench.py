@@ -101,7 +101,16 @@ def place_timed_region(B, ctx, wl, steps):
     return r - back
 
 
-def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, variant_m=True, second_pass=True):
+def buffer_pool(wl, dev):
+    """One set of state and gradient buffers for a series of runs of the same shape.  The time of a launch depends
+    on which physical pages the buffers got (the same code at the same virtual addresses: 0.87 to 0.93 ms between
+    fresh allocations, +-0.1 % within one), so a series that is to be compared point by point keeps its buffers."""
+    import torch
+    return {"shape": (wl.W, wl.ld),
+            **{k: torch.zeros(wl.W, wl.ld, device=dev, dtype=torch.float32) for k in ("x", "e", "m", "g1", "g2")}}
+
+
+def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, variant_m=True, second_pass=True, pool=None):
     """Time `steps` iterations on one workload; returns the fields of the JSON line."""
     import torch
     from paper_2007_13221_amd import binding as B
@@ -110,11 +119,18 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
     dev = torch.device("cuda:0")
     momentum = wl.momentum if variant_m else 0.0
     cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, momentum, wl.seed, ld=wl.ld)
-    opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=variant_e, with_momentum=variant_m)
+    if pool is not None:
+        assert pool["shape"] == (wl.W, wl.ld)
+        pool["x"].zero_()
+        pool["x"][:, :wl.d] = I.initial_model_row(wl, dev)
+        opt = B.CSER(cfg, pool["x"], with_error=variant_e, with_momentum=variant_m, e=pool["e"], m=pool["m"])
+        grads = [I.gradient(wl, t, dev, out=pool[f"g{t}"]) for t in (1, 2)]
+    else:
+        opt = B.CSER(cfg, I.initial_model(wl, dev), with_error=variant_e, with_momentum=variant_m)
+        grads = [I.gradient(wl, t, dev) for t in (1, 2)]   # generated outside every timed region
     for item in tune:
         key, value = item.split("=")
         B.cser_set_tuning(opt.ctx, TUNING_KEYS[key], int(value))
-    grads = [I.gradient(wl, t, dev) for t in (1, 2)]   # generated outside every timed region
     stream = torch.cuda.current_stream().cuda_stream
     glist = B.gradient_list([grads[t & 1] for t in range(steps)])
     torch.cuda.synchronize()
@@ -224,7 +240,8 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
     }
     opt.close()
     del opt, grads
-    torch.cuda.empty_cache()
+    if pool is None:
+        torch.cuda.empty_cache()
     return out
 
 
@@ -325,9 +342,10 @@ def main():
     variant_m = not args.variant.endswith("nomomentum")
     if args.sweep or args.table4:
         points = I.sweep_workloads() if args.sweep else I.table4_workloads()
+        pool = buffer_pool(points[0], torch.device("cuda:0"))   # every point has the same W and ld
         for wl in points:
             r = run_workload(wl, wl.steps, 5, args.tune, with_copy=False, variant_e=variant_e, variant_m=variant_m,
-                             second_pass=False)
+                             second_pass=False, pool=pool)
             print(json.dumps(compact(wl, r)), flush=True)
         return
     named = dict(I.WORKLOADS)

@@ -31,7 +31,7 @@ typedef enum cser_tuning_key {
   CSER_TUNE_NONTEMPORAL = 1,       /* -1 (default) non-temporal accesses unless all state fits 256 MiB; 0 never; 1 always */
   CSER_TUNE_FUSE_RESET = 2,        /* 1 (default) on iterations with t mod H = 0 the error reset runs inside the fused-step
                                       kernel (x and e of its blocks make one trip instead of two); 0 separate reset kernel */
-  CSER_TUNE_TILE_WAVES_PER_CU = 3, /* kernel 1: most resident wavefronts per CU; -1 (default) 16 / 18 / no cap for 4 / 3 / 2
+  CSER_TUNE_TILE_WAVES_PER_CU = 3, /* kernel 1: most resident wavefronts per CU; -1 (default) 12 / 18 / no cap for 4 / 3 / 2
                                       load streams per wavefront; 0 no cap */
   CSER_TUNE_SHARED_GROUPS_PER_CU = 4 /* kernel 2 and the reset kernel: most resident workgroups per CU; -1 (default)
                                       max(2, 24 / W); 0 no cap */

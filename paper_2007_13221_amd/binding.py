@@ -264,13 +264,16 @@ def make_config(d, W, block, R_step, R_reset, H, lr, momentum, seed, ld=None) ->
 class CSER:
     """Convenience owner of a context and its state tensors (allocation and lifetime only)."""
 
-    def __init__(self, cfg: cser_config, x, with_error=True, with_momentum=True, stream=None):
+    def __init__(self, cfg: cser_config, x, with_error=True, with_momentum=True, stream=None, e=None, m=None):
+        """e, m: tensors to use for the residual and the momentum (cser_create zero-fills them); allocated here if None."""
         import torch
         assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and tuple(x.shape) == (cfg.W, cfg.ld)
+        for t in (e, m):
+            assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.shape == x.shape)
         self.cfg = cfg
         self.x = x
-        self.e = torch.zeros_like(x) if with_error else None
-        self.m = torch.zeros_like(x) if with_momentum else None
+        self.e = (torch.zeros_like(x) if e is None else e) if with_error else None
+        self.m = (torch.zeros_like(x) if m is None else m) if with_momentum else None
         self.ctx = cser_create(cfg, self.x, self.e, self.m, stream)
 
     def step(self, g, stream=None):

@@ -33,6 +33,7 @@
 
 #include "cser_internal.h"
 
+#include <cmath>
 #include <type_traits>
 
 namespace cser {
@@ -897,17 +898,17 @@ hipError_t cap_by_lds(const void* fn, uint32_t threads, uint32_t needed, uint32_
 
 }  // namespace
 
-// Residency: measured on the large workload at R_step 256, 4 and 2, the one-wavefront kernel is fastest with 14-20
-// resident wavefronts per CU when a wavefront has 4 load streams (g, m, x, e; uncapped, 28 fit and it is 5 % slower),
-// 16-20 with 3, uncapped with 2 (there a cap of 20 costs 4-14 %); the LDS-shared kernels with about 24 wavefronts
-// per CU.
+// Residency: what the memory system rewards is about 48 KiB of loads in flight per CU.  Measured on the large workload
+// (R_step 256, 8, 4, 2), the one-wavefront kernel is fastest with 10-13 resident wavefronts per CU when a wavefront
+// has 4 load streams (g, m, x, e; 16: 0.5-2 % slower, 8: 3-5 % slower, uncapped, where 28 fit: 5 % slower), 14-20 with
+// 3, uncapped with 2 (there a cap of 20 costs 4-14 %); the LDS-shared kernels with about 24 wavefronts per CU.
 hipError_t resolve_caps(uint32_t W, bool has_e, bool has_m, bool nontemporal, const Tuning& tune, Caps* out) {
   *out = Caps();
   hipError_t err = hipSuccess;
   if (W <= 64) {
     const int streams = 2 + (has_e ? 1 : 0) + (has_m ? 1 : 0);
     const uint32_t want = tune.tile_waves_per_cu >= 0 ? static_cast<uint32_t>(tune.tile_waves_per_cu)
-                                                      : (streams >= 4 ? 16u : (streams == 3 ? 18u : 0u));
+                                                      : (streams >= 4 ? 12u : (streams == 3 ? 18u : 0u));
     const void* fn = with_flags(nontemporal, has_e, has_m, [](auto NT, auto E, auto M) {
       return reinterpret_cast<const void*>(&cser_step_tile_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>);
     });
@@ -998,9 +999,15 @@ hipError_t launch_step(const StepParams& p_in, bool vectorised, bool nontemporal
       //     compressor chose, then the LDS-shared kernel the others.  Its workgroups that find nothing to do cost
       //     about 50 us per 100,000 tiles, which sets the lower end of the range.
       // Break-even points measured for W = 3, 6, 8, 12, 16 at R_step = 2 .. 256.
+      // The pair needs tiles that are synchronised as a whole or not at all: with blocks shorter than a tile (256
+      // columns) most tiles hold both kinds, both launches would visit them, and one kernel on its own is faster
+      // (block 64, R_step 2: pair 0.97 ms, LDS-shared kernel 0.83, one-wavefront kernel 0.86).
       const bool wide_runs = p.W == 1 || p.W == 2 || p.W == 4 || p.W == 8;
+      const double blocks_per_tile = p.block >= 256u ? 1.0 : 256.0 / static_cast<double>(p.block);
+      const double mixed_tiles = 1.0 - std::pow(sync_share, blocks_per_tile) - std::pow(1.0 - sync_share, blocks_per_tile);
       if (p.W <= 16 && sync_share >= 0.9) kernel = kKernelShared;
-      else if (p.W <= 16 && sync_share >= (wide_runs ? 0.4 : 0.1)) kernel = kKernelSplit;
+      else if (p.W <= 16 && mixed_tiles > 0.25 && sync_share >= (wide_runs ? 0.5 : 0.1)) kernel = kKernelShared;
+      else if (p.W <= 16 && mixed_tiles <= 0.25 && sync_share >= (wide_runs ? 0.4 : 0.1)) kernel = kKernelSplit;
       else if (p.W <= 64) kernel = kKernelTile;
       else kernel = kKernelGeneral;
     }
