@@ -420,7 +420,7 @@ def test_gpu_run_stays_within_rounding_of_the_float64_oracle():
 
 def test_profile_timers_counters_and_copy_probe():
     dev = torch.device("cuda:0")
-    wl = _wl(d=100000, W=8, H=2)
+    wl = _wl(d=100000, W=8, H=2, block=256)
     cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
     opt = B.CSER(cfg, I.initial_model(wl, dev))
     B.cser_profile_enable(opt.ctx, True)
@@ -430,8 +430,9 @@ def test_profile_timers_counters_and_copy_probe():
     assert B.cser_profile_read(opt.ctx, 0)[1] == 6
     assert B.cser_profile_read(opt.ctx, 1)[1] == 0      # resets ran inside the fused-step kernel
     c = B.cser_measure_counters(opt.ctx)
-    # R_step = 4, R_reset = 2: a quarter of the blocks is synchronised on ordinary iterations (one-wavefront kernel), five
-    # eighths on reset iterations (the one-wavefront kernel takes the local blocks, then the LDS-shared kernel the rest)
+    # R_step = 4, R_reset = 2, blocks of one tile: a quarter of the blocks is synchronised on ordinary iterations
+    # (one-wavefront kernel), five eighths on reset iterations (the one-wavefront kernel takes the local blocks, then
+    # the LDS-shared kernel the rest)
     assert (c["steps"], c["window_draws"], c["resets_fused"], c["resets_separate"]) == (6, 1, 3, 0)
     assert (c["launches_tile"], c["launches_shared"], c["launches_general"], c["launches_split"]) == (3, 0, 0, 3)
     B.cser_profile_clear(opt.ctx)
