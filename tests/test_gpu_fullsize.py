@@ -131,11 +131,14 @@ def run_ranges(wl, steps, fraction, check_mean_model=True, forced_reset=False, w
         not_identical += assert_states_close("m", opt.m[:, c0:c1].cpu().numpy(), o.m)
         compared += c1 - c0
     blocks = sum(b1 - b0 for b0, b1, _, _, _ in oracles)
+    counters = B.cser_measure_counters(opt.ctx)
+    kernels = {k[len("launches_"):]: v for k, v in counters.items() if k.startswith("launches_") and v}
     print(f"\n[full-size parity] {wl.name}: d={wl.d} block={wl.block} R_step={wl.R_step} R_reset={wl.R_reset} H={wl.H} "
           f"steps={steps}{' + forced reset' if forced_reset else ''}: {len(oracles)} ranges, {blocks} of {Bn} blocks "
           f"= {blocks / Bn:.4f} of the blocks ({compared} columns x {wl.W} workers, every element of x"
           f"{', e' if with_error else ''}, m); inside them C_step chose {step_events} (block, iteration) pairs, "
-          f"C_reset {reset_events}; {not_identical} elements not bit-identical")
+          f"C_reset {reset_events}; fused steps by kernel choice {kernels}, resets fused {counters['resets_fused']} / separate "
+          f"{counters['resets_separate']}; {not_identical} elements not bit-identical")
     assert Fraction(blocks, Bn) >= Fraction(fraction).limit_denominator(1 << 20), (blocks, Bn, fraction)
     assert ks == 0 or step_events > 0
     assert reset_events > 0 or not (forced_reset or (wl.H and steps >= wl.H))
