@@ -7,7 +7,7 @@
 //   cser_step_tile_kernel     Get_p + PSync(p, C_step) + the x / e updates of Algorithm 3 in one pass, and on reset
 //                             iterations the error reset as well; one-wavefront workgroups, W <= 64: the default
 //   cser_step_shared_kernel   the same with W-wavefront workgroups and the worker sums staged in LDS (W <= 16);
-//                             taken when most blocks need the worker mean
+//                             taken for the blocks that need the worker mean when they are many
 //   cser_step_general_kernel  the same, one lane per column group walking all workers: any W, any block size
 //   cser_reset_shared_kernel  the error-reset branch of Algorithm 3 on its own (PSync(e, C_reset), x correction)
 //   cser_reset_general_kernel the same for any W and any block size
@@ -24,8 +24,10 @@
 // one-wavefront workgroup one worker's row over 256 columns.  Only the chosen blocks (1 / R_step of them) need
 // the worker mean, which inevitably brings W rows together: in the default kernel the W workgroups of a tile
 // share that work (each takes 1/W of the tile's chosen column groups for all workers, one worker per lane group,
-// the W-way sum being a fixed-order chain of wavefront shuffles); when half of the blocks or more are chosen,
-// the LDS-shared kernel, whose every access is still a contiguous KiB of one row, is the faster one.
+// the W-way sum being a fixed-order chain of wavefront shuffles).  When a large share of the blocks is chosen,
+// the one-wavefront kernel takes only the blocks no compressor chose and the LDS-shared kernel, whose every access
+// is still a contiguous KiB of one row, takes the others in a second launch; when nearly all are chosen the
+// LDS-shared kernel runs alone (launch_step).
 //
 // Arithmetic, identical in every kernel: beta*m+g and beta*m_new+g are single fused multiply-adds, eta multiplies
 // the rounded result, the worker sum starts from worker 0's value and adds workers 1 .. W-1 in order, the mean is
