@@ -62,6 +62,8 @@ def test_two_calls_in_a_row_the_second_with_a_smaller_input():
     (dict(), False, True), (dict(momentum=0.0), True, False), (dict(momentum=0.0), False, False),
     (dict(W=3), True, True), (dict(W=20, d=3000), True, True), (dict(W=70, d=2000), True, True),
     (dict(block=6, d=4099), True, True), (dict(d=4099, block=4), True, True), (dict(R_step=0, H=1), True, True), (dict(H=0), True, True),
+    (dict(block=256, d=40_000, W=8, R_step=2), True, True),    # half of the tiles synchronised: the pair of launches
+    (dict(block=512, d=40_000, W=6, R_step=4, R_reset=1, H=2), True, True),
 ])
 def test_state_variants_worker_counts_and_layouts(kw, with_error, with_momentum):
     wl = _wl(**kw)
