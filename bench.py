@@ -204,6 +204,8 @@ def run_workload(wl, steps, warmup, tune=(), with_copy=True, variant_e=True, var
 
     kind = ("implementation I" if variant_e else "implementation II (no e)") + ("" if variant_m else ", no momentum buffer")
     kernels = {KERNEL_NAMES[k]: delta[k] for k in KERNEL_NAMES if delta[k]}
+    if wl.W > 16 and delta["launches_split"]:    # beyond 16 workers the general kernel takes the synchronised blocks of a pair
+        kernels["cser_step_tile_kernel+cser_step_general_kernel"] = kernels.pop(KERNEL_NAMES["launches_split"])
     traffic, traffic_source = read_traffic(wl.name) if (variant_e and variant_m and not tune) else (None, None)
     whole_bytes = total_step_bytes + total_reset_bytes
     out = {

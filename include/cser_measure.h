@@ -27,7 +27,7 @@ typedef enum cser_tuning_key {
   CSER_TUNE_KERNEL = 0,            /* 0 (default) automatic; 1 one-wavefront workgroups, a worker's row each (W <= 64);
                                       2 W-wavefront workgroups, worker sums staged in LDS (W <= 16); 3 a lane walks all
                                       workers (any W); 4 a pair of launches, 1 on the blocks neither compressor chose and
-                                      2 on the others (W <= 16).  A kernel that does not take the context's W falls back to 0. */
+                                      2 (beyond 16 workers: 3) on the others.  A kernel that does not take the context's W falls back to 0. */
   CSER_TUNE_NONTEMPORAL = 1,       /* -1 (default) non-temporal accesses unless all state fits 256 MiB; 0 never; 1 always */
   CSER_TUNE_FUSE_RESET = 2,        /* 1 (default) on iterations with t mod H = 0 the error reset runs inside the fused-step
                                       kernel (x and e of its blocks make one trip instead of two); 0 separate reset kernel */

@@ -50,7 +50,8 @@ enum StepKernel {
   kKernelTile = 1,     // one-wavefront workgroups, one worker's row per workgroup (W <= 64)
   kKernelShared = 2,   // W-wavefront workgroups, worker sums staged in LDS (W <= 16)
   kKernelGeneral = 3,  // a lane walks all workers (any W, any block size)
-  kKernelSplit = 4     // two launches: kKernelTile on the blocks neither compressor chose, kKernelShared on the others (W <= 16)
+  kKernelSplit = 4     // two launches: kKernelTile on the blocks neither compressor chose, then kKernelShared (W <= 16) or
+                       // kKernelGeneral (more workers) on the others
 };
 
 struct Tuning {

@@ -573,7 +573,9 @@ __global__ __launch_bounds__(256) void cser_step_general_kernel(StepParams a, ui
   if constexpr (V == 4) b = static_cast<uint32_t>(q) / (a.block / 4u);
   else b = static_cast<uint32_t>(col / a.block);
   const bool step_chosen = a.mask[b] != 0;
-  if (a.reset_mask != nullptr && a.reset_mask[b] != 0) step_and_reset_columns<V, HAS_E, HAS_M>(a, col, step_chosen);
+  const bool reset_chosen = a.reset_mask != nullptr && a.reset_mask[b] != 0;
+  if (a.part == kPartSynchronised && !step_chosen && !reset_chosen) return;   // updated by the one-wavefront kernel
+  if (reset_chosen) step_and_reset_columns<V, HAS_E, HAS_M>(a, col, step_chosen);
   else step_columns<V, 4, NT, HAS_E, HAS_M>(a, col, step_chosen);
 }
 
@@ -842,7 +844,7 @@ hipError_t launch_general(const StepParams& p, uint64_t col_begin, uint64_t col_
 
 hipError_t launch_tile(const StepParams& p, uint32_t groups, bool nt, uint32_t lds, hipStream_t s) {
   const uint64_t tiles64 = (static_cast<uint64_t>(groups) + 63) / 64;
-  if (tiles64 * p.W > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;   // the C ABI rejects such sizes at create
+  if (tiles64 * p.W > 0x7FFFFFFFull || p.W > 65535u) return hipErrorInvalidConfiguration;   // launch_step never asks for such a grid
   const dim3 grid(static_cast<uint32_t>(tiles64), p.W), block(64);
   return with_flags(nt, p.e != nullptr, p.m != nullptr, [&](auto NT, auto E, auto M) {
     hipLaunchKernelGGL((cser_step_tile_kernel<decltype(NT)::value, decltype(E)::value, decltype(M)::value>), grid, block, lds, s,
@@ -907,7 +909,7 @@ hipError_t cap_by_lds(const void* fn, uint32_t threads, uint32_t needed, uint32_
 hipError_t resolve_caps(uint32_t W, bool has_e, bool has_m, bool nontemporal, const Tuning& tune, Caps* out) {
   *out = Caps();
   hipError_t err = hipSuccess;
-  if (W <= 64) {
+  {   // the one-wavefront kernel: any W (beyond 64 workers it only ever takes the blocks no compressor chose)
     const int streams = 2 + (has_e ? 1 : 0) + (has_m ? 1 : 0);
     const uint32_t want = tune.tile_waves_per_cu >= 0 ? static_cast<uint32_t>(tune.tile_waves_per_cu)
                                                       : (streams >= 4 ? 12u : (streams == 3 ? 18u : 0u));
@@ -981,6 +983,12 @@ hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint
   return hipGetLastError();
 }
 
+// The one-wavefront kernel's grid is (tiles, W): at most 65,535 workers and 2^31 - 1 workgroups.
+bool tile_grid_fits(const StepParams& p) {
+  const uint64_t tiles = (p.d / 4 + 63) / 64;
+  return p.W <= 65535u && tiles * p.W <= 0x7FFFFFFFull;
+}
+
 hipError_t launch_step(const StepParams& p_in, bool vectorised, bool nontemporal, const Tuning& tune, const Caps& caps,
                        double sync_share, int* used, hipStream_t s) {
   StepParams p = p_in;
@@ -988,30 +996,41 @@ hipError_t launch_step(const StepParams& p_in, bool vectorised, bool nontemporal
   int kernel = kKernelGeneral;
   if (vectorised) {
     kernel = tune.kernel;
-    if (kernel == kKernelTile && p.W > 64) kernel = kKernelAuto;
-    if ((kernel == kKernelShared || kernel == kKernelSplit) && p.W > 16) kernel = kKernelAuto;
+    if (kernel == kKernelTile && p.W > 64) kernel = kKernelAuto;       // its synchronised path gives each of W lane groups a run of 64 / W column groups
+    if (kernel == kKernelShared && p.W > 16) kernel = kKernelAuto;     // W wavefronts per workgroup
+    if (kernel == kKernelSplit && !tile_grid_fits(p)) kernel = kKernelAuto;
     if (kernel == kKernelAuto) {
-      // Three regimes by the share of the blocks that need the worker mean in this launch (measured on the large
-      // workload; algorithmic TB/s of the blocks concerned, W = 8):
+      // By the share of the blocks that need the worker mean in this launch (measured on the large workload;
+      // algorithmic TB/s of the blocks concerned, W = 8):
       //   * the one-wavefront kernel sweeps the other blocks at 6.5-6.7 but handles the synchronised ones at 5
-      //     (1.6-3.1 when 64 / W column groups are not a run of 64 bytes or more: W = 3, 6, 12, 16): best while they are few;
+      //     (1-3 when 64 / W column groups are not a run of 64 bytes or more: W = 3, 6, 12 and everything from 16 on):
+      //     best while they are few;
       //   * the LDS-shared kernel moves the synchronised blocks at 6.0-6.3 and the others, W rows at a time from
       //     one CU, at 5.5-6.0: best when nearly every block is synchronised;
       //   * in between, each kernel does what it is good at: the one-wavefront kernel takes the blocks neither
       //     compressor chose, then the LDS-shared kernel the others.  Its workgroups that find nothing to do cost
-      //     about 50 us per 100,000 tiles, which sets the lower end of the range.
-      // Break-even points measured for W = 3, 6, 8, 12, 16 at R_step = 2 .. 256.
+      //     about 50 us per 100,000 tiles, which sets the lower end of the range;
+      //   * beyond 16 workers the general kernel (5 TB/s on anything) stands in for the LDS-shared one.
+      // Break-even points measured for W = 3, 6, 8, 12, 16, 24, 32, 64 at R_step = 2 .. 256.
       // The pair needs tiles that are synchronised as a whole or not at all: with blocks shorter than a tile (256
       // columns) most tiles hold both kinds, both launches would visit them, and one kernel on its own is faster
       // (block 64, R_step 2: pair 0.97 ms, LDS-shared kernel 0.83, one-wavefront kernel 0.86).
       const bool wide_runs = p.W == 1 || p.W == 2 || p.W == 4 || p.W == 8;
       const double blocks_per_tile = p.block >= 256u ? 1.0 : 256.0 / static_cast<double>(p.block);
       const double mixed_tiles = 1.0 - std::pow(sync_share, blocks_per_tile) - std::pow(1.0 - sync_share, blocks_per_tile);
-      if (p.W <= 16 && sync_share >= 0.9) kernel = kKernelShared;
-      else if (p.W <= 16 && mixed_tiles > 0.25 && sync_share >= (wide_runs ? 0.5 : 0.1)) kernel = kKernelShared;
-      else if (p.W <= 16 && mixed_tiles <= 0.25 && sync_share >= (wide_runs ? 0.4 : 0.1)) kernel = kKernelSplit;
-      else if (p.W <= 64) kernel = kKernelTile;
-      else kernel = kKernelGeneral;
+      if (p.W <= 16) {
+        if (sync_share >= 0.9) kernel = kKernelShared;
+        else if (mixed_tiles > 0.25 && sync_share >= (wide_runs ? 0.5 : 0.1)) kernel = kKernelShared;
+        else if (mixed_tiles <= 0.25 && sync_share >= (wide_runs ? 0.4 : 0.1)) kernel = kKernelSplit;
+        else kernel = kKernelTile;
+      } else if (!tile_grid_fits(p) || sync_share >= 0.9) {
+        kernel = kKernelGeneral;
+      } else if (p.W > 64 || sync_share > 0.0) {   // beyond 16 workers the pair is never slower (W = 24, 32, 64 at R_step 256: +0.3 .. +3 %)
+        kernel = mixed_tiles <= 0.25 ? kKernelSplit : kKernelGeneral;
+        if (kernel == kKernelGeneral && p.W <= 64 && sync_share < 1.0 / 16.0) kernel = kKernelTile;
+      } else {
+        kernel = kKernelTile;
+      }
     }
   }
   if (used) *used = kernel;
@@ -1029,7 +1048,10 @@ hipError_t launch_step(const StepParams& p_in, bool vectorised, bool nontemporal
       p.part = kPartLocal;
       err = launch_tile(p, groups, nontemporal, caps.tile_lds, s);
       p.part = kPartSynchronised;
-      if (err == hipSuccess) err = launch_shared(p, groups, nontemporal, shared_lds, s);
+      if (err == hipSuccess) {
+        if (p.W <= 16) err = launch_shared(p, groups, nontemporal, shared_lds, s);
+        else err = launch_general<4>(p, 0, d4, nontemporal, s);
+      }
       p.part = kPartAll;
     } else {
       err = launch_general<4>(p, 0, d4, nontemporal, s);

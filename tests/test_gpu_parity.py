@@ -220,9 +220,10 @@ def test_results_do_not_depend_on_launch_shape(tuning):
 def test_every_worker_count_in_every_kernel_that_takes_it(W, R_step):
     """The one-wavefront kernel shares a tile's synchronised column groups among its W workgroups in slices of
     floor(64 / W) groups (two rounds when W does not divide 64); the LDS-shared kernel has W wavefronts per
-    workgroup; beyond 64 workers a lane walks the worker axis."""
+    workgroup; the pair of launches gives the synchronised blocks to the LDS-shared kernel up to 16 workers and to
+    the general kernel beyond; beyond 64 workers a lane walks the worker axis."""
     wl = _wl(d=2500, W=W, block=8, R_step=R_step, R_reset=2, H=2, steps=4)
-    kernels = [None] + ([TILE] if W <= 64 else []) + ([SHARED, SPLIT] if W <= 16 else []) + [GENERAL]
+    kernels = [None] + ([TILE] if W <= 64 else []) + ([SHARED] if W <= 16 else []) + [SPLIT, GENERAL]
     for kernel in kernels:
         assert run_pair(wl, 4, tuning=None if kernel is None else {K: kernel}) == 0
         assert run_pair(wl, 4, with_error=False, tuning=None if kernel is None else {K: kernel}) == 0
