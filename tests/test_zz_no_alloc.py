@@ -94,3 +94,36 @@ def test_largest_size_the_array_takes():
     wl = _wl(d=B.CSER_STATIC_MAX_BLOCKS * 4 - 1, W=2, block=4, R_step=3, R_reset=2, H=1, seed=6)
     assert wl.B == B.CSER_STATIC_MAX_BLOCKS
     _same(*_pair(wl, 2))
+
+
+# ---------------------------------------------------------------------------- under HIP graph capture
+# The call allocates nothing, so once its per-device set-up has run it can be recorded into a HIP graph; every replay,
+# with eager work in between, must give what the same eager call gives.
+@pytest.mark.parametrize("kw", [dict(d=50_000, W=4, block=64, R_step=4, R_reset=2, H=2),
+                                dict(d=40_000, W=8, block=256, R_step=2, R_reset=2, H=3)])
+def test_recorded_call_replays_like_the_eager_call(kw):
+    dev = torch.device("cuda:0")
+    wl = I.Workload(name="graph", lr=0.1, momentum=0.9, x_var=1e-2, g_var=1e-2, seed=21, steps=8, **kw)
+    cfg = B.make_config(wl.d, wl.W, wl.block, wl.R_step, wl.R_reset, wl.H, wl.lr, wl.momentum, wl.seed, ld=wl.ld)
+    t_rec = 2 * wl.H if wl.H else 2          # an iteration that carries an error reset as well
+    state = [I.initial_model(wl, dev), torch.zeros(wl.W, wl.ld, device=dev), torch.zeros(wl.W, wl.ld, device=dev)]
+    ref = [s.clone() for s in state]
+    g = I.gradient(wl, 1, dev)
+    B.cser_step_static(cfg, 1, *state, g)    # first call on the device: looks up the array and the launch shapes
+    B.cser_step_static(cfg, 1, *ref, g)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(graph, stream=s):
+            B.cser_step_static(cfg, t_rec, *state, g, stream=s)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        g.copy_(I.gradient(wl, 10 + replay, dev))           # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        B.cser_step_static(cfg, t_rec, *ref, g)
+        torch.cuda.synchronize()
+        for a, b in zip(state, ref):
+            assert torch.equal(a, b), replay
+    assert state[0].abs().max() > 0
