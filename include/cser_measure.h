@@ -52,6 +52,13 @@ typedef struct cser_counters {
 int cser_measure_counters(const cser_ctx* ctx, cser_counters* out);
 
 /*
+ * Which fused-step kernel (1 .. 4 of CSER_TUNE_KERNEL) a configuration's iterations take by default: ordinary
+ * iterations (reset_iteration = 0) and iterations that carry the error reset as well (reset_iteration = 1).  Host
+ * arithmetic only, no device needed.
+ */
+int cser_measure_kernel_choice(const cser_config* cfg, int reset_iteration, int* kernel);
+
+/*
  * Residency the launches of this context get: dynamic LDS bytes requested per workgroup and the number of
  * workgroups the runtime's occupancy calculator fits on a CU with that request (tile kernel: one wavefront
  * per workgroup; shared kernels: W wavefronts per workgroup).  0 where a kernel does not take the context's W.

@@ -20,7 +20,7 @@ EXPORTS = ("cser_create", "cser_step", "cser_step_many", "cser_step_static", "cs
            "cser_preset_csea", "cser_preset_cser_pl", "cser_overall_ratio",
            "cser_block_counts", "cser_set_lr", "cser_get_step", "cser_set_step", "cser_strerror", "cser_last_hip_error")
 MEASURE_EXPORTS = ("cser_profile_enable", "cser_profile_read", "cser_profile_clear", "cser_set_tuning",
-                   "cser_measure_counters", "cser_measure_residency", "cser_copy_probe")
+                   "cser_measure_counters", "cser_measure_residency", "cser_measure_kernel_choice", "cser_copy_probe")
 
 # cser_tuning_key
 CSER_TUNE_KERNEL, CSER_TUNE_NONTEMPORAL, CSER_TUNE_FUSE_RESET = 0, 1, 2
@@ -90,6 +90,7 @@ def _lib():
         L.cser_copy_probe.argtypes = [vp, vp, u64, vp]
         L.cser_measure_counters.argtypes = [vp, ctypes.POINTER(cser_counters)]
         L.cser_measure_residency.argtypes = [vp, ctypes.POINTER(cser_residency)]
+        L.cser_measure_kernel_choice.argtypes = [ctypes.POINTER(cser_config), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         L.cser_strerror.argtypes = [ctypes.c_int]
         L.cser_strerror.restype = ctypes.c_char_p
         L.cser_last_hip_error.argtypes = []
@@ -246,6 +247,14 @@ def cser_measure_residency(ctx):
     r = cser_residency()
     _check(_lib().cser_measure_residency(ctx, ctypes.byref(r)), "cser_measure_residency")
     return {n: getattr(r, n) for n, _ in cser_residency._fields_}
+
+
+def cser_measure_kernel_choice(cfg: cser_config, reset_iteration=False) -> int:
+    """The fused-step kernel (KERNEL_TILE, KERNEL_SHARED, KERNEL_GENERAL or KERNEL_SPLIT) an iteration of cfg takes."""
+    k = ctypes.c_int()
+    _check(_lib().cser_measure_kernel_choice(ctypes.byref(cfg), int(bool(reset_iteration)), ctypes.byref(k)),
+           "cser_measure_kernel_choice")
+    return k.value
 
 
 def cser_copy_probe(dst, src, n_bytes, stream=None):

@@ -641,6 +641,16 @@ int cser_measure_residency(const cser_ctx* ctx, cser_residency* out) {
   return CSER_OK;
 }
 
+int cser_measure_kernel_choice(const cser_config* cfg, int reset_iteration, int* kernel) {
+  if (!cfg || !kernel || cfg->d == 0 || cfg->W == 0 || cfg->block == 0 || cfg->R_reset == 0) return CSER_EINVAL;
+  const uint64_t B = ceil_div(cfg->d, cfg->block);
+  const uint32_t k_step = cfg->R_step == 0 ? 0u : static_cast<uint32_t>(ceil_div(B, cfg->R_step));
+  const uint32_t k_reset = static_cast<uint32_t>(ceil_div(B, cfg->R_reset));
+  *kernel = cser::choose_step_kernel(cfg->d, cfg->W, cfg->block, cfg->block % 4 == 0,
+                                     sync_share(B, k_step, k_reset, reset_iteration != 0), cser::Tuning());
+  return CSER_OK;
+}
+
 int cser_copy_probe(void* dst, const void* src, uint64_t n_bytes, void* hip_stream) {
   if (!dst || !src) return CSER_EINVAL;
   if (!aligned(dst, 16) || !aligned(src, 16) || n_bytes % 16 != 0) return CSER_EALIGN;

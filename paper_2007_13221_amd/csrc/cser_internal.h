@@ -86,6 +86,10 @@ constexpr uint32_t kOrderedListCounts = 1024;
 hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint32_t* counts, uint32_t* idx_sorted,
                                hipStream_t s);
 
+// Which kernel launch_step takes (a StepKernel other than kKernelAuto) for a launch in which `sync_share` of the
+// blocks need the worker mean.  Host arithmetic only.
+int choose_step_kernel(uint64_t d, uint32_t W, uint32_t block, bool vectorised, double sync_share, const Tuning& tune);
+
 // Fused Get_p + PSync(p, C_step) + x/e update over columns [0, d) (and the error reset when p.reset_mask is set).
 // `vectorised` requires block to be a multiple of 4 columns (rows need only 4-byte alignment).  `sync_share`:
 // expected share of the blocks that need the worker mean in this launch.  *used (may be null) receives the kernel taken.

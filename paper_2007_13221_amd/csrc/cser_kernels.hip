@@ -984,55 +984,54 @@ hipError_t launch_ordered_list(const uint8_t* mask, uint32_t B, uint32_t k, uint
 }
 
 // The one-wavefront kernel's grid is (tiles, W): at most 65,535 workers and 2^31 - 1 workgroups.
-bool tile_grid_fits(const StepParams& p) {
-  const uint64_t tiles = (p.d / 4 + 63) / 64;
-  return p.W <= 65535u && tiles * p.W <= 0x7FFFFFFFull;
+bool tile_grid_fits(uint64_t d, uint32_t W) {
+  const uint64_t tiles = (d / 4 + 63) / 64;
+  return W <= 65535u && tiles * W <= 0x7FFFFFFFull;
+}
+
+int choose_step_kernel(uint64_t d, uint32_t W, uint32_t block, bool vectorised, double sync_share, const Tuning& tune) {
+  if (!vectorised) return kKernelGeneral;
+  int kernel = tune.kernel;
+  if (kernel == kKernelTile && W > 64) kernel = kKernelAuto;       // its synchronised path gives each of W lane groups a run of 64 / W column groups
+  if (kernel == kKernelShared && W > 16) kernel = kKernelAuto;     // W wavefronts per workgroup
+  if (kernel == kKernelSplit && !tile_grid_fits(d, W)) kernel = kKernelAuto;
+  if (kernel != kKernelAuto) return kernel;
+  // By the share of the blocks that need the worker mean in this launch (measured on the large workload;
+  // algorithmic TB/s of the blocks concerned, W = 8):
+  //   * the one-wavefront kernel sweeps the other blocks at 6.5-6.7 but handles the synchronised ones at 5
+  //     (1-3 when 64 / W column groups are not a run of 64 bytes or more: W = 3, 6, 12 and everything from 16 on):
+  //     best while they are few;
+  //   * the LDS-shared kernel moves the synchronised blocks at 6.0-6.3 and the others, W rows at a time from
+  //     one CU, at 5.5-6.0: best when nearly every block is synchronised;
+  //   * in between, each kernel does what it is good at: the one-wavefront kernel takes the blocks neither
+  //     compressor chose, then the LDS-shared kernel the others.  Its workgroups that find nothing to do cost
+  //     about 50 us per 100,000 tiles, which sets the lower end of the range;
+  //   * beyond 16 workers the general kernel (5 TB/s on anything) stands in for the LDS-shared one.
+  // Break-even points measured for W = 3, 6, 8, 12, 16, 24, 32, 64, 96 at R_step = 2 .. 256.
+  // The pair needs tiles that are synchronised as a whole or not at all: with blocks shorter than a tile (256
+  // columns) most tiles hold both kinds, both launches would visit them, and one kernel on its own is faster
+  // (block 64, R_step 2: pair 0.97 ms, LDS-shared kernel 0.83, one-wavefront kernel 0.86).
+  const bool wide_runs = W == 1 || W == 2 || W == 4 || W == 8;
+  const double blocks_per_tile = block >= 256u ? 1.0 : 256.0 / static_cast<double>(block);
+  const double mixed_tiles = 1.0 - std::pow(sync_share, blocks_per_tile) - std::pow(1.0 - sync_share, blocks_per_tile);
+  if (W <= 16) {
+    if (sync_share >= 0.9) return kKernelShared;
+    if (mixed_tiles > 0.25 && sync_share >= (wide_runs ? 0.5 : 0.1)) return kKernelShared;
+    if (mixed_tiles <= 0.25 && sync_share >= (wide_runs ? 0.4 : 0.1)) return kKernelSplit;
+    return kKernelTile;
+  }
+  if (!tile_grid_fits(d, W) || sync_share >= 0.9) return kKernelGeneral;
+  if (W > 64 || sync_share > 0.0) {   // beyond 16 workers the pair is never slower (W = 24, 32, 64 at R_step 256: +0.3 .. +3 %)
+    return mixed_tiles <= 0.25 ? kKernelSplit : kKernelGeneral;
+  }
+  return kKernelTile;
 }
 
 hipError_t launch_step(const StepParams& p_in, bool vectorised, bool nontemporal, const Tuning& tune, const Caps& caps,
                        double sync_share, int* used, hipStream_t s) {
   StepParams p = p_in;
   p.part = kPartAll;
-  int kernel = kKernelGeneral;
-  if (vectorised) {
-    kernel = tune.kernel;
-    if (kernel == kKernelTile && p.W > 64) kernel = kKernelAuto;       // its synchronised path gives each of W lane groups a run of 64 / W column groups
-    if (kernel == kKernelShared && p.W > 16) kernel = kKernelAuto;     // W wavefronts per workgroup
-    if (kernel == kKernelSplit && !tile_grid_fits(p)) kernel = kKernelAuto;
-    if (kernel == kKernelAuto) {
-      // By the share of the blocks that need the worker mean in this launch (measured on the large workload;
-      // algorithmic TB/s of the blocks concerned, W = 8):
-      //   * the one-wavefront kernel sweeps the other blocks at 6.5-6.7 but handles the synchronised ones at 5
-      //     (1-3 when 64 / W column groups are not a run of 64 bytes or more: W = 3, 6, 12 and everything from 16 on):
-      //     best while they are few;
-      //   * the LDS-shared kernel moves the synchronised blocks at 6.0-6.3 and the others, W rows at a time from
-      //     one CU, at 5.5-6.0: best when nearly every block is synchronised;
-      //   * in between, each kernel does what it is good at: the one-wavefront kernel takes the blocks neither
-      //     compressor chose, then the LDS-shared kernel the others.  Its workgroups that find nothing to do cost
-      //     about 50 us per 100,000 tiles, which sets the lower end of the range;
-      //   * beyond 16 workers the general kernel (5 TB/s on anything) stands in for the LDS-shared one.
-      // Break-even points measured for W = 3, 6, 8, 12, 16, 24, 32, 64 at R_step = 2 .. 256.
-      // The pair needs tiles that are synchronised as a whole or not at all: with blocks shorter than a tile (256
-      // columns) most tiles hold both kinds, both launches would visit them, and one kernel on its own is faster
-      // (block 64, R_step 2: pair 0.97 ms, LDS-shared kernel 0.83, one-wavefront kernel 0.86).
-      const bool wide_runs = p.W == 1 || p.W == 2 || p.W == 4 || p.W == 8;
-      const double blocks_per_tile = p.block >= 256u ? 1.0 : 256.0 / static_cast<double>(p.block);
-      const double mixed_tiles = 1.0 - std::pow(sync_share, blocks_per_tile) - std::pow(1.0 - sync_share, blocks_per_tile);
-      if (p.W <= 16) {
-        if (sync_share >= 0.9) kernel = kKernelShared;
-        else if (mixed_tiles > 0.25 && sync_share >= (wide_runs ? 0.5 : 0.1)) kernel = kKernelShared;
-        else if (mixed_tiles <= 0.25 && sync_share >= (wide_runs ? 0.4 : 0.1)) kernel = kKernelSplit;
-        else kernel = kKernelTile;
-      } else if (!tile_grid_fits(p) || sync_share >= 0.9) {
-        kernel = kKernelGeneral;
-      } else if (p.W > 64 || sync_share > 0.0) {   // beyond 16 workers the pair is never slower (W = 24, 32, 64 at R_step 256: +0.3 .. +3 %)
-        kernel = mixed_tiles <= 0.25 ? kKernelSplit : kKernelGeneral;
-        if (kernel == kKernelGeneral && p.W <= 64 && sync_share < 1.0 / 16.0) kernel = kKernelTile;
-      } else {
-        kernel = kKernelTile;
-      }
-    }
-  }
+  const int kernel = choose_step_kernel(p.d, p.W, p.block, vectorised, sync_share, tune);
   if (used) *used = kernel;
   if (!vectorised) return launch_general<1>(p, 0, p.d, nontemporal, s);
   const uint64_t d4 = p.d & ~3ull;

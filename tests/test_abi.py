@@ -98,3 +98,32 @@ def test_presets_of_the_special_cases():
     cfg = B.make_config(1000, 8, 10, 0, 4, 0, 0.1, 0.0, 0)
     assert B.cser_overall_ratio(cfg) == float("inf")
     assert B._lib().cser_preset_csea(None) == B.CSER_EINVAL
+
+
+def test_default_kernel_by_worker_count_block_size_and_synchronised_share():
+    """Host logic of the launch: which fused-step kernel an iteration takes by default (measured break-even points;
+    every choice computes the same bits, which the GPU parity tests check)."""
+    T, S, G, P = B.KERNEL_TILE, B.KERNEL_SHARED, B.KERNEL_GENERAL, B.KERNEL_SPLIT
+
+    def choice(reset=False, **kw):
+        base = dict(d=25_557_032, W=8, block=1024, R_step=256, R_reset=16, H=32, lr=0.1, momentum=0.9, seed=2)
+        base.update(kw)
+        return B.cser_measure_kernel_choice(B.make_config(**base), reset)
+
+    assert choice() == T and choice(reset=True) == T                   # the large workload: few blocks synchronised
+    assert choice(R_step=8) == T and choice(R_step=4) == T
+    assert choice(R_step=2) == P                                       # half of the blocks: pair of launches
+    assert choice(R_step=2, block=4096) == P and choice(R_step=2, block=256) == P
+    assert choice(R_step=2, block=64) == S                             # tiles hold both kinds of blocks: one kernel
+    assert choice(R_step=1) == S                                       # everything synchronised
+    assert choice(R_step=4, R_reset=2, reset=True) == P and choice(R_step=4, R_reset=2) == T   # Table 4's first row
+    assert choice(R_step=0, R_reset=1, reset=True) == S and choice(R_step=0, R_reset=1) == T   # local SGD with period H
+    for W in (3, 6, 12, 16):
+        assert choice(W=W, R_step=256) == T and choice(W=W, R_step=8) == P and choice(W=W, R_step=1) == S
+    for W in (17, 32, 64, 96, 1000):
+        assert choice(W=W, R_step=256) == P and choice(W=W, R_step=2) == P and choice(W=W, R_step=1) == G
+    assert choice(W=32, R_step=0) == T and choice(W=96, R_step=0) == P  # nothing synchronised; beyond 64 workers only the pair's first half fits
+    assert choice(W=32, R_step=32, block=64) == P and choice(W=32, R_step=4, block=64) == G   # short blocks: few / many tiles hold both kinds
+    assert choice(block=6) == G and choice(block=1022) == G            # not a multiple of 4 columns: element-wise kernels
+    assert choice(W=70_000) == G                                       # more workers than a grid dimension takes
+    assert B._lib().cser_measure_kernel_choice(None, 0, None) == B.CSER_EINVAL
