@@ -187,6 +187,15 @@ def test_table4_compressor_configurations_full_size(wl):
     run_ranges(wl, max(2 * wl.H, 8), 1 / 64, check_mean_model=False, max_ranges=8)
 
 
+@pytest.mark.parametrize("W,R_step", [(3, 4), (12, 2), (32, 8), (70, 64)])
+def test_other_worker_counts_full_size(W, R_step):
+    """Worker counts whose synchronised blocks take other paths at this size: the pair of launches with the LDS-shared
+    kernel (3, 12 workers) and with the general kernel (32, 70 workers; beyond 64 the one-wavefront kernel only ever
+    takes the blocks no compressor chose)."""
+    wl = replace(I.WORKLOADS["large_cnn"], name=f"W{W}", W=W, R_step=R_step, R_reset=4, H=4, seed=8)
+    run_ranges(wl, 9, 1 / 128, check_mean_model=False, max_ranges=6)
+
+
 def test_transformer_sized_stress_20_steps_and_forced_reset():
     # 20 steps are fewer than H = 64, so the reset is forced once at the end, as the workload prescribes
     wl = I.WORKLOADS["transformer"]
