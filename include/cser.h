@@ -37,6 +37,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+#if defined(__GNUC__)
+#pragma GCC visibility push(default) /* the library is built with hidden visibility: only these entry points are exported */
+#endif
 
 typedef enum cser_status {
   CSER_OK = 0,
@@ -169,6 +172,9 @@ int cser_step_static(const cser_config* cfg, uint64_t t, float* x, float* e, flo
 const char* cser_strerror(int status);
 const char* cser_last_hip_error(void); /* text of the last HIP error seen by this thread, "" if none */
 
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+#if defined(__GNUC__)
+#pragma GCC visibility push(default) /* the library is built with hidden visibility: only these entry points are exported */
+#endif
 
 /*
  * Per-kernel timing.  When enabled, every launch of the fused-step kernel (which = 0) and of the
@@ -78,6 +81,9 @@ int cser_measure_residency(const cser_ctx* ctx, cser_residency* out);
  */
 int cser_copy_probe(void* dst, const void* src, uint64_t n_bytes, void* hip_stream);
 
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
 #ifdef __cplusplus
 }
 #endif

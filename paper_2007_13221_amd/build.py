@@ -15,7 +15,7 @@ HEADERS = [os.path.join(CSRC, "cser_internal.h"), os.path.join(os.path.dirname(H
            os.path.join(os.path.dirname(HERE), "include", "cser_measure.h")]
 LIBRARY = os.path.join(HERE, "libcser_hip.so")
 
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 
 
